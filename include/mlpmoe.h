@@ -1,0 +1,192 @@
+/*
+ * mlpmoe.h -- C ABI of the MI355X (gfx950) branched SwiGLU MLP forward.
+ *
+ * The operation (MLPMoE, Sec. 3.1):
+ *
+ *     branch_b(x) = alpha_b * W_down^(b) [ SiLU(W_gate^(b) x) (.) W_up^(b) x ]
+ *     MLPMoE(x)   = sum_{b=0}^{B-1} branch_b(x)
+ *
+ * where the B branches are contiguous slices of the intermediate dimension,
+ * d_inter = sum_b d_b.  Branches removed by Compensated Branch Pruning
+ * (Sec. 3.3) are skipped, and neurons removed by per-branch differential
+ * sparsity (Sec. 3.2, structured form) are compacted out of the weight
+ * buffers, so the widths d_b may differ from branch to branch.
+ *
+ * Layouts (all row-major, no padding between rows):
+ *     x       [T, d_model]
+ *     W_gate  [d_inter, d_model]    row j          = neuron j
+ *     W_up    [d_inter, d_model]    row j          = neuron j
+ *     W_down  [d_model, d_inter]    column j       = neuron j
+ *     out     [T, d_model]          float, overwritten (never accumulated into)
+ * Branch b owns neurons branch_offsets[b] .. branch_offsets[b+1]-1.
+ *
+ * Pointer kinds: x, W_*, out, workspaces and gather lists passed to
+ * mlpmoe_compact are DEVICE pointers owned by the caller; branch_offsets,
+ * alpha and active_mask are HOST pointers, read during the call and free for
+ * reuse when it returns.  `stream` is a hipStream_t passed as void* (NULL =
+ * the default stream).  Forward calls enqueue work and return without
+ * synchronising.
+ *
+ * Every function returns MLPMOE_OK (0) or a negative MLPMOE_ERR_* code.
+ * Argument errors are detected on the host before anything is enqueued; the
+ * library never throws, aborts or prints.
+ */
+#ifndef MLPMOE_H
+#define MLPMOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MLPMOE_MAX_BRANCHES 64
+
+/* Exported-symbol marker: the library is built with hidden visibility by default. */
+#if defined(__GNUC__)
+#define MLPMOE_API __attribute__((visibility("default")))
+#else
+#define MLPMOE_API
+#endif
+
+enum {
+    MLPMOE_OK = 0,
+    MLPMOE_ERR_NULL = -1,        /* a required pointer is NULL                              */
+    MLPMOE_ERR_SHAPE = -2,       /* a size is negative, zero where it may not be, or too big */
+    MLPMOE_ERR_OFFSETS = -3,     /* offsets do not start at 0, decrease, or miss d_inter    */
+    MLPMOE_ERR_UNSUPPORTED = -4, /* the requested kernel path cannot run these arguments    */
+    MLPMOE_ERR_WORKSPACE = -5,   /* workspace missing, too small or misaligned              */
+    MLPMOE_ERR_HIP = -6,         /* a HIP runtime call failed                               */
+    MLPMOE_ERR_ALIGN = -7        /* a device pointer is not 16-byte aligned                 */
+};
+
+/* Kernel path selection for the *_ws entry points. */
+enum {
+    MLPMOE_PATH_AUTO = 0,    /* library picks: decode for T <= 16, MFMA otherwise, generic if unaligned */
+    MLPMOE_PATH_GENERIC = 1, /* LDS-tiled FMA kernels: any shape and alignment                        */
+    MLPMOE_PATH_MFMA = 2,    /* bf16 MFMA prefill kernels (needs d_model%8==0 and offsets%8==0)       */
+    MLPMOE_PATH_DECODE = 3   /* weight-streaming kernels, T <= 16 (same alignment needs as MFMA)      */
+};
+
+/* Human-readable name of a status code (static string, never NULL). */
+MLPMOE_API const char *mlpmoe_status_string(int status);
+
+/*
+ * mlpmoe_slice -- host only; touches no GPU.
+ * Builds the branch table of one MLP (Sec. 3.1 slicing, Sec. 3.1 scalar gates,
+ * Sec. 3.3 pruning rule).
+ *
+ *   d_inter, B    intermediate width of the dense MLP and number of branches,
+ *                 1 <= B <= MLPMOE_MAX_BRANCHES, d_inter >= 0.  Branch b gets
+ *                 floor(d_inter/B) neurons, the first d_inter mod B branches one more.
+ *   K_keep        0 or >= B: every branch active, alpha_b = 1.
+ *                 0 < K_keep < B: keep the first K_keep branches with
+ *                 alpha_b = sqrt(B / K_keep); the rest get alpha_b = 0, active_mask 0.
+ *   neuron_keep   NULL, or d_inter bytes: neuron j survives iff neuron_keep[j] != 0.
+ *                 Surviving neurons keep their order; d_b becomes the survivor count.
+ *   pad_to        >= 1.  Each branch width is rounded up to a multiple of pad_to with
+ *                 padding rows (gather index -1, to be filled with zeros: a zero gate/up
+ *                 row and a zero down column contribute exactly nothing).  The MFMA and
+ *                 decode paths need pad_to to be a multiple of 8.
+ *   branch_offsets [B+1] out: prefix sums of the (padded) widths; [B] is the row count
+ *                 of the compacted layer.
+ *   alpha [B] out, active_mask [B] out.
+ *   gather_index  NULL, or room for gather_capacity entries: source neuron of every
+ *                 compacted row, or -1 for a padding row.
+ *   gather_capacity  entries available in gather_index; d_inter + B*(pad_to-1) always suffices.
+ * Errors: NULL (outputs), SHAPE (B, d_inter, pad_to out of range; gather_capacity too small).
+ */
+MLPMOE_API int mlpmoe_slice(int d_inter, int B, int K_keep, const uint8_t *neuron_keep, int pad_to,
+                 int32_t *branch_offsets, float *alpha, uint8_t *active_mask,
+                 int32_t *gather_index, int gather_capacity);
+
+/*
+ * mlpmoe_compact -- applies a gather list on the device (weight preparation, not
+ * part of the per-token path).  For r in [0, n_rows):
+ *     W_gate_c[r, :] = gather[r] >= 0 ? W_gate[gather[r], :] : 0      (same for W_up)
+ *     W_down_c[:, r] = gather[r] >= 0 ? W_down[:, gather[r]] : 0
+ * elem_bytes is 2 (bf16) or 4 (float).  Source buffers have d_inter_src neurons;
+ * destination buffers have n_rows neurons and must not overlap the sources.
+ * gather is a DEVICE pointer to n_rows int32 values, each -1 or in [0, d_inter_src)
+ * (the caller guarantees the range; it is not re-checked on the device).
+ */
+MLPMOE_API int mlpmoe_compact(const void *W_gate, const void *W_up, const void *W_down, const int32_t *gather,
+                   int n_rows, int d_model, int d_inter_src, int elem_bytes, void *W_gate_c,
+                   void *W_up_c, void *W_down_c, void *stream);
+
+/*
+ * Bytes of device workspace a forward call with these sizes may use (gated
+ * intermediate H[T, d_inter] plus split-K partial sums).  Independent of the
+ * branch table.  Returns 0 for invalid sizes.
+ */
+MLPMOE_API size_t mlpmoe_workspace_bytes(int T, int d_model, int d_inter, int B, int elem_bytes);
+
+/*
+ * mlpmoe_forward_bf16 -- MLPMoE(x) of Sec. 3.1 for bf16 x and weights, float out.
+ *
+ *   x, W_gate, W_up, W_down   device, bf16, layouts above, 16-byte aligned bases.
+ *   branch_offsets [B+1], alpha [B], active_mask [B]   host.  active_mask[b] == 0:
+ *       branch b contributes nothing and none of its weights are read (non-finite
+ *       values inside it cannot reach out).  alpha_b == 0 with the mask set is
+ *       computed like any other value.
+ *   T >= 0 tokens (T == 0 is a no-op), d_model >= 1, d_inter = branch_offsets[B] >= 0,
+ *   1 <= B <= MLPMOE_MAX_BRANCHES.  d_b == 0 is legal.
+ *   out    device float [T, d_model]; every element is written (zeros if nothing is active).
+ *
+ * Arithmetic: gate and up products accumulate in fp32; h = alpha_b * SiLU(g) * u is
+ * formed in fp32 and rounded ONCE to bf16 (nearest even); the down projection
+ * accumulates those bf16 values against W_down in fp32 across all branches.
+ * Results are bitwise reproducible from run to run (no floating-point atomics).
+ *
+ * Workspace: taken from a per-device buffer the library owns and grows with
+ * hipMalloc when a call needs more than any earlier one (that growth synchronises
+ * the device).  Calls that overlap in time on one device must use the *_ws form
+ * with distinct workspaces.
+ *
+ * Errors: NULL, SHAPE, OFFSETS, ALIGN, WORKSPACE (allocation failed), HIP.
+ */
+MLPMOE_API int mlpmoe_forward_bf16(const void *x, const void *W_gate, const void *W_up, const void *W_down,
+                        const int32_t *branch_offsets, const float *alpha,
+                        const uint8_t *active_mask, int T, int d_model, int d_inter, int B,
+                        float *out, void *stream);
+
+/* Same operation and signature; the storage type defaults to bf16. */
+MLPMOE_API int mlpmoe_forward(const void *x, const void *W_gate, const void *W_up, const void *W_down,
+                   const int32_t *branch_offsets, const float *alpha, const uint8_t *active_mask,
+                   int T, int d_model, int d_inter, int B, float *out, void *stream);
+
+/*
+ * mlpmoe_forward_f32 -- same operation for float x and weights; no intermediate
+ * rounding, fp32 accumulation throughout (LDS-tiled FMA kernels, any shape).
+ */
+MLPMOE_API int mlpmoe_forward_f32(const float *x, const float *W_gate, const float *W_up, const float *W_down,
+                       const int32_t *branch_offsets, const float *alpha,
+                       const uint8_t *active_mask, int T, int d_model, int d_inter, int B,
+                       float *out, void *stream);
+
+/*
+ * Caller-owned workspace forms.  workspace: device pointer, 256-byte aligned, at
+ * least mlpmoe_workspace_bytes(T, d_model, d_inter, B, elem_bytes) bytes; its
+ * contents are scratch.  path: one of MLPMOE_PATH_*; a path that cannot run the
+ * given arguments returns MLPMOE_ERR_UNSUPPORTED and enqueues nothing.
+ * These calls never allocate device memory.
+ */
+MLPMOE_API int mlpmoe_forward_bf16_ws(const void *x, const void *W_gate, const void *W_up, const void *W_down,
+                           const int32_t *branch_offsets, const float *alpha,
+                           const uint8_t *active_mask, int T, int d_model, int d_inter, int B,
+                           float *out, void *workspace, size_t workspace_bytes, int path,
+                           void *stream);
+
+MLPMOE_API int mlpmoe_forward_f32_ws(const float *x, const float *W_gate, const float *W_up,
+                          const float *W_down, const int32_t *branch_offsets, const float *alpha,
+                          const uint8_t *active_mask, int T, int d_model, int d_inter, int B,
+                          float *out, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Frees the library-owned per-device workspaces (synchronises each device first). */
+MLPMOE_API int mlpmoe_release(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MLPMOE_H */

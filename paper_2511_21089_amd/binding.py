@@ -1,0 +1,203 @@
+"""ctypes binding of libmlpmoe.so: argument marshalling only.
+
+Function names mirror include/mlpmoe.h.  Tensors are torch tensors on the GPU
+(PyTorch supplies device memory and streams, nothing else); branch tables are
+numpy arrays / sequences on the host.  Importing this module loads the shared
+library and raises if it has not been built: there is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libmlpmoe.so")
+
+OK = 0
+ERR_NULL, ERR_SHAPE, ERR_OFFSETS, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, ERR_ALIGN = -1, -2, -3, -4, -5, -6, -7
+PATH_AUTO, PATH_GENERIC, PATH_MFMA, PATH_DECODE = 0, 1, 2, 3
+MAX_BRANCHES = 64
+
+EXPORTS = ["mlpmoe_status_string", "mlpmoe_slice", "mlpmoe_compact", "mlpmoe_workspace_bytes",
+           "mlpmoe_forward_bf16", "mlpmoe_forward", "mlpmoe_forward_f32", "mlpmoe_forward_bf16_ws",
+           "mlpmoe_forward_f32_ws", "mlpmoe_release"]
+
+
+class MlpMoeError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %s (%d)" % (where, status_string(status), status))
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        # nothing built yet: build once (hipcc cross-compiles; no GPU needed)
+        _build.build(force=True)
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, ip, fp, bp = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p
+    i, sz = ctypes.c_int, ctypes.c_size_t
+    lib.mlpmoe_status_string.argtypes = [i]
+    lib.mlpmoe_status_string.restype = ctypes.c_char_p
+    lib.mlpmoe_slice.argtypes = [i, i, i, bp, i, ip, fp, bp, ip, i]
+    lib.mlpmoe_slice.restype = i
+    lib.mlpmoe_compact.argtypes = [vp, vp, vp, vp, i, i, i, i, vp, vp, vp, vp]
+    lib.mlpmoe_compact.restype = i
+    lib.mlpmoe_workspace_bytes.argtypes = [i, i, i, i, i]
+    lib.mlpmoe_workspace_bytes.restype = sz
+    fwd = [vp, vp, vp, vp, ip, fp, bp, i, i, i, i, vp, vp]
+    for name in ("mlpmoe_forward_bf16", "mlpmoe_forward", "mlpmoe_forward_f32"):
+        getattr(lib, name).argtypes = fwd
+        getattr(lib, name).restype = i
+    lib.mlpmoe_forward_bf16_ws.argtypes = [vp, vp, vp, vp, ip, fp, bp, i, i, i, i, vp, vp, sz, i, vp]
+    lib.mlpmoe_forward_bf16_ws.restype = i
+    lib.mlpmoe_forward_f32_ws.argtypes = [vp, vp, vp, vp, ip, fp, bp, i, i, i, i, vp, vp, sz, vp]
+    lib.mlpmoe_forward_f32_ws.restype = i
+    lib.mlpmoe_release.argtypes = []
+    lib.mlpmoe_release.restype = i
+    return lib
+
+
+lib = _load()
+
+
+def status_string(status: int) -> str:
+    return lib.mlpmoe_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str):
+    if status != OK:
+        raise MlpMoeError(status, where)
+
+
+def _host(a, dtype):
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+def _dev_ptr(t):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous GPU tensor")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream_ptr(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+# --------------------------------------------------------------------------- host-only
+def mlpmoe_slice(d_inter: int, B: int, K_keep: int = 0, neuron_keep=None, pad_to: int = 1):
+    """Branch table of one MLP.  Returns (branch_offsets[B+1], alpha[B], active_mask[B], gather_index)."""
+    n = max(int(B), 0)
+    off = np.zeros(n + 1, dtype=np.int32)
+    alpha = np.zeros(n, dtype=np.float32)
+    mask = np.zeros(n, dtype=np.uint8)
+    cap = max(int(d_inter), 0) + n * max(int(pad_to) - 1, 0)
+    gather = np.full(max(cap, 1), -2, dtype=np.int32)
+    keep = None if neuron_keep is None else _host(neuron_keep, np.uint8)
+    if keep is not None and keep.shape != (d_inter,):
+        raise ValueError("neuron_keep must have d_inter entries")
+    rc = lib.mlpmoe_slice(int(d_inter), int(B), int(K_keep), None if keep is None else keep.ctypes.data,
+                          int(pad_to), off.ctypes.data, alpha.ctypes.data, mask.ctypes.data,
+                          gather.ctypes.data, cap)
+    _check(rc, "mlpmoe_slice")
+    return off, alpha, mask, gather[: int(off[-1])].copy()
+
+
+def mlpmoe_workspace_bytes(T, d_model, d_inter, B, elem_bytes=2) -> int:
+    return int(lib.mlpmoe_workspace_bytes(int(T), int(d_model), int(d_inter), int(B), int(elem_bytes)))
+
+
+# --------------------------------------------------------------------------- device
+def mlpmoe_compact(W_gate, W_up, W_down, gather_index, stream=None):
+    """Compacted copies of the three weight matrices (rows of gate/up, columns of down)."""
+    import torch
+    d_inter_src, d_model = W_gate.shape
+    g = gather_index if hasattr(gather_index, "is_cuda") else torch.as_tensor(
+        np.ascontiguousarray(gather_index, dtype=np.int32), device=W_gate.device)
+    n_rows = int(g.numel())
+    Wg_c = torch.empty((n_rows, d_model), dtype=W_gate.dtype, device=W_gate.device)
+    Wu_c = torch.empty((n_rows, d_model), dtype=W_gate.dtype, device=W_gate.device)
+    Wd_c = torch.empty((d_model, n_rows), dtype=W_gate.dtype, device=W_gate.device)
+    rc = lib.mlpmoe_compact(_dev_ptr(W_gate), _dev_ptr(W_up), _dev_ptr(W_down), _dev_ptr(g), n_rows,
+                            int(d_model), int(d_inter_src), int(W_gate.element_size()),
+                            _dev_ptr(Wg_c), _dev_ptr(Wu_c), _dev_ptr(Wd_c), _stream_ptr(stream))
+    _check(rc, "mlpmoe_compact")
+    return Wg_c, Wu_c, Wd_c
+
+
+def _table(branch_offsets, alpha, active_mask):
+    off = _host(branch_offsets, np.int32)
+    al = _host(alpha, np.float32)
+    mk = _host(active_mask, np.uint8)
+    B = off.shape[0] - 1
+    if al.shape != (B,) or mk.shape != (B,):
+        raise ValueError("alpha and active_mask need B entries, branch_offsets B+1")
+    return off, al, mk, B
+
+
+def _forward(name, x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, out, stream,
+             workspace=None, path=None):
+    import torch
+    off, al, mk, B = _table(branch_offsets, alpha, active_mask)
+    T, d_model = x.shape
+    d_inter = W_gate.shape[0]
+    if out is None:
+        out = torch.empty((T, d_model), dtype=torch.float32, device=x.device)
+    args = [_dev_ptr(x), _dev_ptr(W_gate), _dev_ptr(W_up), _dev_ptr(W_down), off.ctypes.data,
+            al.ctypes.data, mk.ctypes.data, int(T), int(d_model), int(d_inter), int(B), _dev_ptr(out)]
+    if workspace is not None:
+        args += [_dev_ptr(workspace), workspace.numel() * workspace.element_size()]
+        if path is not None:
+            args.append(int(path))
+    args.append(_stream_ptr(stream))
+    _check(getattr(lib, name)(*args), name)
+    return out
+
+
+def mlpmoe_forward_bf16(x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, out=None, stream=None):
+    return _forward("mlpmoe_forward_bf16", x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, out, stream)
+
+
+def mlpmoe_forward(x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, out=None, stream=None):
+    return _forward("mlpmoe_forward", x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, out, stream)
+
+
+def mlpmoe_forward_f32(x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, out=None, stream=None):
+    return _forward("mlpmoe_forward_f32", x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, out, stream)
+
+
+def mlpmoe_forward_bf16_ws(x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, workspace,
+                           path=PATH_AUTO, out=None, stream=None):
+    return _forward("mlpmoe_forward_bf16_ws", x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask,
+                    out, stream, workspace=workspace, path=path)
+
+
+def mlpmoe_forward_f32_ws(x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, workspace,
+                          out=None, stream=None):
+    return _forward("mlpmoe_forward_f32_ws", x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask,
+                    out, stream, workspace=workspace)
+
+
+def mlpmoe_release():
+    _check(lib.mlpmoe_release(), "mlpmoe_release")
+
+
+def new_workspace(T, d_model, d_inter, B, elem_bytes=2, device="cuda"):
+    """A torch byte tensor large enough for one forward call (256-byte aligned by the allocator)."""
+    import torch
+    return torch.empty(mlpmoe_workspace_bytes(T, d_model, d_inter, B, elem_bytes), dtype=torch.uint8,
+                       device=device)
+
+
+def bf16_tensor(bits: np.ndarray, device="cuda"):
+    """Upload bf16 bit patterns (uint16 numpy) as a torch.bfloat16 tensor."""
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(device)
+    return t.view(torch.bfloat16)

@@ -1,0 +1,58 @@
+// Internal declarations shared by the host API and the kernel translation units.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "mlpmoe.h"
+
+namespace mlpmoe {
+
+constexpr int kMaxRuns = MLPMOE_MAX_BRANCHES / 2 + 1;
+
+// Branch table of one call, passed to kernels by value (kernel-argument memory).
+// A "run" is a maximal range of neurons covered by consecutive active, non-empty
+// branches: since alpha_b is folded into the gated intermediate, the down
+// projection may sweep a whole run without looking at branch boundaries.
+struct BranchTable {
+    int B;
+    int n_runs;
+    int d_eff;                               // neurons in active branches
+    int off[MLPMOE_MAX_BRANCHES + 1];
+    float alpha[MLPMOE_MAX_BRANCHES];
+    unsigned long long active;               // bit b set: branch b is computed
+    int run_start[kMaxRuns];
+    int run_end[kMaxRuns];
+};
+
+struct FwdArgs {
+    const void *x, *Wg, *Wu, *Wd;
+    float *out;
+    int T, d_model, d_inter;
+    void *H;            // gated intermediate [T, ldh], bf16 or float
+    int ldh;
+    float *partial;     // split-K partial sums, or nullptr
+    size_t partial_bytes;
+    hipStream_t stream;
+};
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// Leading dimension of the intermediate H (elements).
+inline int h_ld(int d_inter) { return (int)align_up((size_t)(d_inter > 0 ? d_inter : 1), 64); }
+
+// Split-K factor of the MFMA down projection for an output of T x d_model and kt K-tiles.
+int mfma_down_splits(int T, int d_model, int k_elems);
+size_t mfma_partial_bytes(int T, int d_model, int d_inter);
+
+hipError_t launch_fill_zero(float *out, size_t n, hipStream_t s);
+hipError_t launch_generic(const FwdArgs &a, const BranchTable &bt, bool is_bf16);
+hipError_t launch_mfma_bf16(const FwdArgs &a, const BranchTable &bt);
+hipError_t launch_decode_bf16(const FwdArgs &a, const BranchTable &bt);
+hipError_t launch_compact(const void *Wg, const void *Wu, const void *Wd, const int32_t *gather,
+                          int n_rows, int d_model, int d_inter_src, int elem_bytes, void *Wg_c,
+                          void *Wu_c, void *Wd_c, hipStream_t s);
+
+}  // namespace mlpmoe

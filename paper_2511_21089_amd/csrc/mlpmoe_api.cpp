@@ -1,0 +1,327 @@
+// Host side of the C ABI: argument validation, the slicing rules, the branch
+// table, workspace management and kernel-path dispatch.  No arithmetic of the
+// forward itself lives here.
+#include <math.h>
+#include <string.h>
+
+#include <map>
+#include <mutex>
+
+#include "internal.h"
+
+using namespace mlpmoe;
+
+namespace {
+
+struct DeviceWorkspace {
+    void *ptr = nullptr;
+    size_t bytes = 0;
+};
+std::mutex g_ws_mutex;
+std::map<int, DeviceWorkspace> g_ws;
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int validate_common(const void *x, const void *Wg, const void *Wu, const void *Wd,
+                    const int32_t *off, const float *alpha, const uint8_t *mask, int T, int d_model,
+                    int d_inter, int B, const float *out)
+{
+    if (!off || !alpha || !mask) return MLPMOE_ERR_NULL;
+    if (B < 1 || B > MLPMOE_MAX_BRANCHES || T < 0 || d_model < 1 || d_inter < 0)
+        return MLPMOE_ERR_SHAPE;
+    // index arithmetic inside the kernels is 32-bit for rows and columns, 64-bit for addresses
+    if ((long long)T * d_model > (1LL << 40) || (long long)d_inter * d_model > (1LL << 40) ||
+        d_model > (1 << 24) || d_inter > (1 << 24) || T > (1 << 24))
+        return MLPMOE_ERR_SHAPE;
+    if (off[0] != 0) return MLPMOE_ERR_OFFSETS;
+    for (int b = 0; b < B; ++b)
+        if (off[b + 1] < off[b]) return MLPMOE_ERR_OFFSETS;
+    if (off[B] != d_inter) return MLPMOE_ERR_OFFSETS;
+    if (T == 0) return MLPMOE_OK;
+    if (!x || !out) return MLPMOE_ERR_NULL;
+    if (d_inter > 0 && (!Wg || !Wu || !Wd)) return MLPMOE_ERR_NULL;
+    if (!aligned16(x) || !aligned16(out) || !aligned16(Wg) || !aligned16(Wu) || !aligned16(Wd))
+        return MLPMOE_ERR_ALIGN;
+    return MLPMOE_OK;
+}
+
+void build_table(const int32_t *off, const float *alpha, const uint8_t *mask, int B, BranchTable &bt)
+{
+    memset(&bt, 0, sizeof(bt));
+    bt.B = B;
+    for (int b = 0; b <= B; ++b) bt.off[b] = off[b];
+    int runs = 0;
+    for (int b = 0; b < B; ++b) {
+        bt.alpha[b] = alpha[b];
+        if (!mask[b]) continue;
+        bt.active |= 1ULL << b;
+        if (off[b + 1] == off[b]) continue;
+        bt.d_eff += off[b + 1] - off[b];
+        if (runs > 0 && bt.run_end[runs - 1] == off[b]) {
+            bt.run_end[runs - 1] = off[b + 1];
+        } else {
+            bt.run_start[runs] = off[b];
+            bt.run_end[runs] = off[b + 1];
+            ++runs;
+        }
+    }
+    bt.n_runs = runs;
+}
+
+bool fast_path_aligned(const BranchTable &bt, int d_model, int d_inter)
+{
+    if (d_model % 8 != 0 || d_inter % 8 != 0) return false;
+    for (int r = 0; r < bt.n_runs; ++r)
+        if (bt.run_start[r] % 8 != 0 || bt.run_end[r] % 8 != 0) return false;
+    return true;
+}
+
+size_t h_bytes(int T, int d_inter, int elem_bytes)
+{
+    return align_up((size_t)T * (size_t)h_ld(d_inter) * (size_t)elem_bytes, 256);
+}
+
+int forward_impl(const void *x, const void *Wg, const void *Wu, const void *Wd, const int32_t *off,
+                 const float *alpha, const uint8_t *mask, int T, int d_model, int d_inter, int B,
+                 float *out, void *workspace, size_t workspace_bytes, int path, bool is_bf16,
+                 hipStream_t stream)
+{
+    int rc = validate_common(x, Wg, Wu, Wd, off, alpha, mask, T, d_model, d_inter, B, out);
+    if (rc != MLPMOE_OK) return rc;
+    if (path < MLPMOE_PATH_AUTO || path > MLPMOE_PATH_DECODE) return MLPMOE_ERR_UNSUPPORTED;
+    if (T == 0) return MLPMOE_OK;
+
+    BranchTable bt;
+    build_table(off, alpha, mask, B, bt);
+
+    if (bt.n_runs == 0) {   // nothing active: the sum over branches is empty
+        return launch_fill_zero(out, (size_t)T * d_model, stream) == hipSuccess ? MLPMOE_OK
+                                                                                : MLPMOE_ERR_HIP;
+    }
+
+    const bool aligned = is_bf16 && fast_path_aligned(bt, d_model, d_inter);
+    if (path == MLPMOE_PATH_AUTO)
+        path = !aligned ? MLPMOE_PATH_GENERIC : (T <= 16 ? MLPMOE_PATH_DECODE : MLPMOE_PATH_MFMA);
+    if (path != MLPMOE_PATH_GENERIC && !aligned) return MLPMOE_ERR_UNSUPPORTED;
+    if (path == MLPMOE_PATH_DECODE && T > 16) return MLPMOE_ERR_UNSUPPORTED;
+
+    const int elem = is_bf16 ? 2 : 4;
+    const size_t need = mlpmoe_workspace_bytes(T, d_model, d_inter, B, elem);
+    if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+        return MLPMOE_ERR_WORKSPACE;
+
+    FwdArgs a;
+    a.x = x; a.Wg = Wg; a.Wu = Wu; a.Wd = Wd; a.out = out;
+    a.T = T; a.d_model = d_model; a.d_inter = d_inter;
+    a.H = workspace;
+    a.ldh = h_ld(d_inter);
+    a.partial_bytes = need - h_bytes(T, d_inter, elem);
+    a.partial = a.partial_bytes
+                    ? reinterpret_cast<float *>(static_cast<char *>(workspace) + h_bytes(T, d_inter, elem))
+                    : nullptr;
+    a.stream = stream;
+
+    hipError_t e;
+    if (path == MLPMOE_PATH_GENERIC) e = launch_generic(a, bt, is_bf16);
+    else if (path == MLPMOE_PATH_MFMA) e = launch_mfma_bf16(a, bt);
+    else e = launch_decode_bf16(a, bt);
+    return e == hipSuccess ? MLPMOE_OK : MLPMOE_ERR_HIP;
+}
+
+// Library-owned workspace of the current device, grown on demand.
+int owned_workspace(size_t need, void **ptr, size_t *bytes)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return MLPMOE_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_ws_mutex);
+    DeviceWorkspace &w = g_ws[dev];
+    if (w.bytes < need) {
+        if (w.ptr) {
+            if (hipDeviceSynchronize() != hipSuccess) return MLPMOE_ERR_HIP;
+            (void)hipFree(w.ptr);
+            w.ptr = nullptr;
+            w.bytes = 0;
+        }
+        void *p = nullptr;
+        if (hipMalloc(&p, need) != hipSuccess) {
+            (void)hipGetLastError();
+            return MLPMOE_ERR_WORKSPACE;
+        }
+        w.ptr = p;
+        w.bytes = need;
+    }
+    *ptr = w.ptr;
+    *bytes = w.bytes;
+    return MLPMOE_OK;
+}
+
+int forward_owned(const void *x, const void *Wg, const void *Wu, const void *Wd, const int32_t *off,
+                  const float *alpha, const uint8_t *mask, int T, int d_model, int d_inter, int B,
+                  float *out, bool is_bf16, hipStream_t stream)
+{
+    int rc = validate_common(x, Wg, Wu, Wd, off, alpha, mask, T, d_model, d_inter, B, out);
+    if (rc != MLPMOE_OK) return rc;
+    if (T == 0) return MLPMOE_OK;
+    size_t need = mlpmoe_workspace_bytes(T, d_model, d_inter, B, is_bf16 ? 2 : 4);
+    void *ws = nullptr;
+    size_t ws_bytes = 0;
+    rc = owned_workspace(need, &ws, &ws_bytes);
+    if (rc != MLPMOE_OK) return rc;
+    return forward_impl(x, Wg, Wu, Wd, off, alpha, mask, T, d_model, d_inter, B, out, ws, ws_bytes,
+                        MLPMOE_PATH_AUTO, is_bf16, stream);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *mlpmoe_status_string(int status)
+{
+    switch (status) {
+    case MLPMOE_OK: return "ok";
+    case MLPMOE_ERR_NULL: return "null pointer";
+    case MLPMOE_ERR_SHAPE: return "bad size";
+    case MLPMOE_ERR_OFFSETS: return "bad branch offsets";
+    case MLPMOE_ERR_UNSUPPORTED: return "kernel path cannot run these arguments";
+    case MLPMOE_ERR_WORKSPACE: return "workspace missing, too small or misaligned";
+    case MLPMOE_ERR_HIP: return "HIP runtime error";
+    case MLPMOE_ERR_ALIGN: return "device pointer not 16-byte aligned";
+    default: return "unknown status";
+    }
+}
+
+int mlpmoe_slice(int d_inter, int B, int K_keep, const uint8_t *neuron_keep, int pad_to,
+                 int32_t *branch_offsets, float *alpha, uint8_t *active_mask, int32_t *gather_index,
+                 int gather_capacity)
+{
+    if (!branch_offsets || !alpha || !active_mask) return MLPMOE_ERR_NULL;
+    if (B < 1 || B > MLPMOE_MAX_BRANCHES || d_inter < 0 || d_inter > (1 << 24) || pad_to < 1 ||
+        pad_to > 4096 || K_keep < 0)
+        return MLPMOE_ERR_SHAPE;
+    if (gather_index && gather_capacity < 0) return MLPMOE_ERR_SHAPE;
+
+    // Sec. 3.3: keep the first K branches, rescale them by sqrt(B/K); the others are switched off.
+    const bool prune = K_keep > 0 && K_keep < B;
+    const float keep_alpha = prune ? (float)sqrt((double)B / (double)K_keep) : 1.0f;
+    for (int b = 0; b < B; ++b) {
+        const bool on = !prune || b < K_keep;
+        alpha[b] = on ? keep_alpha : 0.0f;
+        active_mask[b] = on ? 1 : 0;
+    }
+
+    // Sec. 3.1: contiguous slices; survivors of each slice are packed in order, then padded.
+    const int base = d_inter / B, rem = d_inter % B;
+    int src = 0, dst = 0;
+    branch_offsets[0] = 0;
+    for (int b = 0; b < B; ++b) {
+        const int width = base + (b < rem ? 1 : 0);
+        int kept = 0;
+        for (int j = src; j < src + width; ++j) {
+            if (neuron_keep && !neuron_keep[j]) continue;
+            if (gather_index) {
+                if (dst + kept >= gather_capacity) return MLPMOE_ERR_SHAPE;
+                gather_index[dst + kept] = j;
+            }
+            ++kept;
+        }
+        const int padded = (kept + pad_to - 1) / pad_to * pad_to;
+        if (gather_index) {
+            if (dst + padded > gather_capacity) return MLPMOE_ERR_SHAPE;
+            for (int r = kept; r < padded; ++r) gather_index[dst + r] = -1;
+        }
+        src += width;
+        dst += padded;
+        branch_offsets[b + 1] = dst;
+    }
+    return MLPMOE_OK;
+}
+
+int mlpmoe_compact(const void *W_gate, const void *W_up, const void *W_down, const int32_t *gather,
+                   int n_rows, int d_model, int d_inter_src, int elem_bytes, void *W_gate_c,
+                   void *W_up_c, void *W_down_c, void *stream)
+{
+    if (n_rows < 0 || d_model < 1 || d_inter_src < 0 || (elem_bytes != 2 && elem_bytes != 4))
+        return MLPMOE_ERR_SHAPE;
+    if (n_rows == 0) return MLPMOE_OK;
+    if (!W_gate || !W_up || !W_down || !gather || !W_gate_c || !W_up_c || !W_down_c)
+        return MLPMOE_ERR_NULL;
+    hipError_t e = launch_compact(W_gate, W_up, W_down, gather, n_rows, d_model, d_inter_src,
+                                  elem_bytes, W_gate_c, W_up_c, W_down_c,
+                                  static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? MLPMOE_OK : MLPMOE_ERR_HIP;
+}
+
+size_t mlpmoe_workspace_bytes(int T, int d_model, int d_inter, int B, int elem_bytes)
+{
+    if (T < 0 || d_model < 1 || d_inter < 0 || B < 1 || B > MLPMOE_MAX_BRANCHES ||
+        (elem_bytes != 2 && elem_bytes != 4))
+        return 0;
+    if (T == 0) return 256;
+    size_t bytes = h_bytes(T, d_inter, elem_bytes);
+    if (elem_bytes == 2) bytes += mfma_partial_bytes(T, d_model, d_inter);
+    return bytes + 256;
+}
+
+int mlpmoe_forward_bf16_ws(const void *x, const void *W_gate, const void *W_up, const void *W_down,
+                           const int32_t *branch_offsets, const float *alpha,
+                           const uint8_t *active_mask, int T, int d_model, int d_inter, int B,
+                           float *out, void *workspace, size_t workspace_bytes, int path, void *stream)
+{
+    return forward_impl(x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, T, d_model,
+                        d_inter, B, out, workspace, workspace_bytes, path, true,
+                        static_cast<hipStream_t>(stream));
+}
+
+int mlpmoe_forward_f32_ws(const float *x, const float *W_gate, const float *W_up, const float *W_down,
+                          const int32_t *branch_offsets, const float *alpha,
+                          const uint8_t *active_mask, int T, int d_model, int d_inter, int B,
+                          float *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return forward_impl(x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, T, d_model,
+                        d_inter, B, out, workspace, workspace_bytes, MLPMOE_PATH_AUTO, false,
+                        static_cast<hipStream_t>(stream));
+}
+
+int mlpmoe_forward_bf16(const void *x, const void *W_gate, const void *W_up, const void *W_down,
+                        const int32_t *branch_offsets, const float *alpha,
+                        const uint8_t *active_mask, int T, int d_model, int d_inter, int B, float *out,
+                        void *stream)
+{
+    return forward_owned(x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, T, d_model,
+                         d_inter, B, out, true, static_cast<hipStream_t>(stream));
+}
+
+int mlpmoe_forward(const void *x, const void *W_gate, const void *W_up, const void *W_down,
+                   const int32_t *branch_offsets, const float *alpha, const uint8_t *active_mask, int T,
+                   int d_model, int d_inter, int B, float *out, void *stream)
+{
+    return mlpmoe_forward_bf16(x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, T,
+                               d_model, d_inter, B, out, stream);
+}
+
+int mlpmoe_forward_f32(const float *x, const float *W_gate, const float *W_up, const float *W_down,
+                       const int32_t *branch_offsets, const float *alpha, const uint8_t *active_mask,
+                       int T, int d_model, int d_inter, int B, float *out, void *stream)
+{
+    return forward_owned(x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, T, d_model,
+                         d_inter, B, out, false, static_cast<hipStream_t>(stream));
+}
+
+int mlpmoe_release(void)
+{
+    std::lock_guard<std::mutex> lock(g_ws_mutex);
+    int rc = MLPMOE_OK;
+    int cur = 0;
+    (void)hipGetDevice(&cur);
+    for (auto &kv : g_ws) {
+        if (!kv.second.ptr) continue;
+        if (hipSetDevice(kv.first) != hipSuccess || hipDeviceSynchronize() != hipSuccess ||
+            hipFree(kv.second.ptr) != hipSuccess)
+            rc = MLPMOE_ERR_HIP;
+        kv.second = DeviceWorkspace();
+    }
+    (void)hipSetDevice(cur);
+    return rc;
+}
+
+}  // extern "C"

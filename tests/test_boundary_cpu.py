@@ -1,0 +1,134 @@
+"""Host-side checks of the C-ABI library that need no GPU: exported symbols, the slicing
+call against its oracle, and argument validation (errors are reported before any GPU work)."""
+import ctypes
+import math
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2511_21089_amd import binding as mm
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    names = []
+    inc = os.path.join(ROOT, "include")
+    for fn in sorted(os.listdir(inc)):
+        if fn.endswith(".h"):
+            text = open(os.path.join(inc, fn)).read()
+            names += re.findall(r"MLPMOE_API\s+[\w\s\*]+?\b(mlpmoe_\w+)\s*\(", text)
+    return names
+
+
+def test_every_declared_symbol_is_exported():
+    names = declared_functions()
+    assert len(names) >= 10 and len(set(names)) == len(names)
+    for n in names:
+        assert hasattr(mm.lib, n), n
+    assert sorted(names) == sorted(mm.EXPORTS)
+
+
+def test_status_strings():
+    assert mm.status_string(0) == "ok"
+    for code in range(-7, 0):
+        assert mm.status_string(code) not in ("ok", "unknown status")
+    assert mm.status_string(-99) == "unknown status"
+
+
+@pytest.mark.parametrize("d_inter,B,K,pad", [(4864, 8, 0, 1), (4864, 8, 6, 1), (14336, 16, 0, 8), (100, 7, 3, 4),
+                                             (5, 8, 0, 1), (4864, 16, 16, 1), (14336, 32, 24, 32), (0, 3, 0, 1)])
+def test_slice_matches_oracle(d_inter, B, K, pad):
+    rng = np.random.default_rng(d_inter + B)
+    for keep in (None, (rng.uniform(size=d_inter) < 0.7).astype(np.uint8)):
+        off, alpha, mask, gather = mm.mlpmoe_slice(d_inter, B, K, keep, pad)
+        o_off, o_alpha, o_mask, o_gather = oracle.slice_plan(d_inter, B, K, keep, pad)
+        assert np.array_equal(off, o_off)
+        assert np.array_equal(mask, o_mask)
+        assert np.array_equal(gather, o_gather)
+        assert np.allclose(alpha, o_alpha, rtol=1e-7, atol=0)
+        assert np.all(np.diff(off) % pad == 0)
+
+
+def test_slice_compensated_alpha_closed_form():
+    _, alpha, mask, _ = mm.mlpmoe_slice(4864, 8, 6)
+    assert alpha[0] == np.float32(math.sqrt(8 / 6)) and alpha[7] == 0 and list(mask) == [1] * 6 + [0, 0]
+
+
+def test_slice_errors():
+    off = np.zeros(5, np.int32)
+    al = np.zeros(4, np.float32)
+    mk = np.zeros(4, np.uint8)
+    f = mm.lib.mlpmoe_slice
+    assert f(16, 4, 0, None, 1, None, al.ctypes.data, mk.ctypes.data, None, 0) == mm.ERR_NULL
+    assert f(16, 0, 0, None, 1, off.ctypes.data, al.ctypes.data, mk.ctypes.data, None, 0) == mm.ERR_SHAPE
+    assert f(16, 65, 0, None, 1, off.ctypes.data, al.ctypes.data, mk.ctypes.data, None, 0) == mm.ERR_SHAPE
+    assert f(-1, 4, 0, None, 1, off.ctypes.data, al.ctypes.data, mk.ctypes.data, None, 0) == mm.ERR_SHAPE
+    assert f(16, 4, 0, None, 0, off.ctypes.data, al.ctypes.data, mk.ctypes.data, None, 0) == mm.ERR_SHAPE
+    g = np.zeros(8, np.int32)
+    assert f(16, 4, 0, None, 1, off.ctypes.data, al.ctypes.data, mk.ctypes.data, g.ctypes.data, 8) == mm.ERR_SHAPE
+    assert f(16, 4, 0, None, 1, off.ctypes.data, al.ctypes.data, mk.ctypes.data, None, 0) == mm.OK
+
+
+def test_workspace_bytes():
+    assert mm.mlpmoe_workspace_bytes(0, 64, 256, 4) > 0
+    assert mm.mlpmoe_workspace_bytes(-1, 64, 256, 4) == 0
+    assert mm.mlpmoe_workspace_bytes(4, 64, 256, 4, elem_bytes=3) == 0
+    a = mm.mlpmoe_workspace_bytes(4096, 4096, 14336, 16)
+    assert a >= 4096 * 14336 * 2
+
+
+def _fwd_args(off, al, mk, T=4, d_model=64, d_inter=256, B=4, x=0x1000, w=0x1000, out=0x1000):
+    vp = ctypes.c_void_p
+    return [vp(x), vp(w), vp(w), vp(w), off.ctypes.data, al.ctypes.data, mk.ctypes.data, T, d_model,
+            d_inter, B, vp(out)]
+
+
+def test_forward_argument_validation_needs_no_gpu():
+    """Bad arguments are rejected on the host; the fake device addresses are never touched."""
+    off = np.array([0, 64, 128, 192, 256], np.int32)
+    al = np.ones(4, np.float32)
+    mk = np.ones(4, np.uint8)
+    ws = [ctypes.c_void_p(0x1000), 1 << 30, mm.PATH_AUTO, None]
+    f = mm.lib.mlpmoe_forward_bf16_ws
+    assert f(*(_fwd_args(off, al, mk, B=0) + ws)) == mm.ERR_SHAPE
+    assert f(*(_fwd_args(off, al, mk, B=65) + ws)) == mm.ERR_SHAPE
+    assert f(*(_fwd_args(off, al, mk, T=-1) + ws)) == mm.ERR_SHAPE
+    assert f(*(_fwd_args(off, al, mk, d_model=0) + ws)) == mm.ERR_SHAPE
+    assert f(*(_fwd_args(off, al, mk, d_inter=255) + ws)) == mm.ERR_OFFSETS
+    bad = off.copy()
+    bad[0] = 1
+    assert f(*(_fwd_args(bad, al, mk) + ws)) == mm.ERR_OFFSETS
+    bad = np.array([0, 128, 64, 192, 256], np.int32)
+    assert f(*(_fwd_args(bad, al, mk) + ws)) == mm.ERR_OFFSETS
+    assert f(*(_fwd_args(off, al, mk, x=0) + ws)) == mm.ERR_NULL
+    assert f(*(_fwd_args(off, al, mk, out=0) + ws)) == mm.ERR_NULL
+    assert f(*(_fwd_args(off, al, mk, w=0) + ws)) == mm.ERR_NULL
+    assert f(*(_fwd_args(off, al, mk, x=0x1008) + ws)) == mm.ERR_ALIGN
+    a = _fwd_args(off, al, mk)
+    a[4] = None
+    assert f(*(a + ws)) == mm.ERR_NULL
+    # T == 0 is a successful no-op even with null tensors
+    assert f(*(_fwd_args(off, al, mk, T=0, x=0, out=0) + ws)) == mm.OK
+    assert mm.lib.mlpmoe_forward_f32_ws(*(_fwd_args(off, al, mk, T=0) + ws[:2] + [None])) == mm.OK
+    # workspace problems and impossible paths are host-side errors too
+    assert f(*(_fwd_args(off, al, mk) + [None, 0, mm.PATH_AUTO, None])) == mm.ERR_WORKSPACE
+    assert f(*(_fwd_args(off, al, mk) + [ctypes.c_void_p(0x1000), 16, mm.PATH_AUTO, None])) == mm.ERR_WORKSPACE
+    assert f(*(_fwd_args(off, al, mk) + [ctypes.c_void_p(0x1010), 1 << 30, mm.PATH_AUTO, None])) == mm.ERR_WORKSPACE
+    assert f(*(_fwd_args(off, al, mk) + [ctypes.c_void_p(0x1000), 1 << 30, 9, None])) == mm.ERR_UNSUPPORTED
+    assert f(*(_fwd_args(off, al, mk, T=17) + [ctypes.c_void_p(0x1000), 1 << 30, mm.PATH_DECODE, None])) == mm.ERR_UNSUPPORTED
+    odd = np.array([0, 60, 128, 192, 256], np.int32)      # branch boundary not a multiple of 8 ...
+    mk2 = np.array([1, 0, 1, 1], np.uint8)                # ... and exposed as a run boundary
+    assert f(*(_fwd_args(odd, al, mk2) + [ctypes.c_void_p(0x1000), 1 << 30, mm.PATH_MFMA, None])) == mm.ERR_UNSUPPORTED
+
+
+def test_compact_validation():
+    vp = ctypes.c_void_p
+    f = mm.lib.mlpmoe_compact
+    assert f(vp(16), vp(16), vp(16), vp(16), 4, 8, 8, 3, vp(16), vp(16), vp(16), None) == mm.ERR_SHAPE
+    assert f(vp(16), vp(16), vp(16), vp(16), -1, 8, 8, 2, vp(16), vp(16), vp(16), None) == mm.ERR_SHAPE
+    assert f(None, vp(16), vp(16), vp(16), 4, 8, 8, 2, vp(16), vp(16), vp(16), None) == mm.ERR_NULL
+    assert f(None, None, None, None, 0, 8, 8, 2, None, None, None, None) == mm.OK

@@ -1,0 +1,225 @@
+"""GPU parity: every kernel path of the C-ABI library against the CPU oracle, element by element.
+
+Tolerances (max|err| / rms(oracle)): 1e-5 for float storage, 1e-2 for bf16 storage with fp32
+accumulation.  bf16 paths are gated against the oracle's contract mode (same single rounding of
+alpha*h to bf16) and, additionally, against its exact mode.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from gpu_util import BF16_TOL, FP32_TOL, oracle_out, run_gpu, to_dev
+from paper_2511_21089_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def mm():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2511_21089_amd import binding
+    return binding
+
+
+def equal_offsets(d_inter, B):
+    return (np.arange(B + 1) * (d_inter // B)).astype(np.int32)
+
+
+# ------------------------------------------------------------------ float path
+def test_tiny_f32_equals_dense_mlp(mm):
+    """d_model 64, d_inter 256, B=4, T=32, alpha=1, all active: must equal the dense MLP."""
+    L = synth.make_layer("tiny_f32", 32, seed=0)
+    off, alpha, mask, _ = mm.mlpmoe_slice(256, 4)
+    got = run_gpu(L.x, L.W_gate, L.W_up, L.W_down, off, alpha, mask)
+    dense = oracle.dense_swiglu(L.x, L.W_gate, L.W_up, L.W_down)
+    ref = oracle_out(L.x, L.W_gate, L.W_up, L.W_down, off, alpha, mask, "exact")
+    assert oracle.rel_max_err(got, dense) <= FP32_TOL
+    assert oracle.rel_max_err(got, ref) <= FP32_TOL
+
+
+@pytest.mark.parametrize("T,dm,di,off,mask", [
+    (70, 50, 130, [0, 33, 33, 77, 130], [1, 1, 0, 1]),          # ragged everything, empty + pruned branch
+    (1, 7, 5, [0, 5], [1]),
+    (129, 64, 192, [0, 64, 128, 192], [0, 1, 1]),
+])
+def test_f32_general_shapes(mm, T, dm, di, off, mask):
+    rng = np.random.default_rng(T + dm)
+    x, Wg, Wu, Wd = synth.random_layer(rng, T, dm, di, w_scale=0.1)
+    off = np.array(off, np.int32)
+    mask = np.array(mask, np.uint8)
+    alpha = rng.uniform(0.5, 1.5, size=len(mask)).astype(np.float32)
+    got = run_gpu(x, Wg, Wu, Wd, off, alpha, mask)
+    ref = oracle_out(x, Wg, Wu, Wd, off, alpha, mask, "exact")
+    assert oracle.rel_max_err(got, ref) <= FP32_TOL
+
+
+# ------------------------------------------------------------------ bf16 paths at sizes spanning tiles + tails
+def check_bf16(got, args):
+    ref_c = oracle_out(*args, "contract")
+    ref_e = oracle_out(*args, "exact")
+    e_c, e_e = oracle.rel_max_err(got, ref_c), oracle.rel_max_err(got, ref_e)
+    assert np.all(np.isfinite(got))
+    assert e_c <= BF16_TOL, ("contract", e_c)
+    assert e_e <= BF16_TOL, ("exact", e_e)
+    return e_c, e_e
+
+
+def small_bf16_case(seed, T, dm, off, mask, w_scale=0.08):
+    rng = np.random.default_rng(seed)
+    di = off[-1]
+    x, Wg, Wu, Wd = synth.random_layer(rng, T, dm, di, dtype="bf16", w_scale=w_scale)
+    alpha = rng.uniform(0.9, 1.2, size=len(mask)).astype(np.float32)
+    return x, Wg, Wu, Wd, np.array(off, np.int32), alpha, np.array(mask, np.uint8)
+
+
+def test_bf16_generic_unaligned_branches(mm):
+    args = small_bf16_case(1, 75, 72, [0, 37, 37, 101, 150, 203], [1, 1, 0, 1, 1])
+    got = run_gpu(*args, path=mm.PATH_GENERIC)
+    check_bf16(got, args)
+    # the automatic choice must route unaligned tables to the same kernels
+    assert np.array_equal(run_gpu(*args), got)
+
+
+MFMA_CASES = [
+    # T, d_model, offsets, mask
+    (300, 136, [0, 136, 136, 400, 520], [1, 1, 0, 1]),     # 2 M tiles with tail, K tail (136 = 2*64+8), runs
+    (64, 64, [0, 128], [1]),
+    (257, 264, [0, 8, 264, 272, 600], [1, 0, 1, 1]),       # 8-wide branch, run starting mid tile
+    (40, 512, [0, 256, 512, 768], [1, 1, 1]),              # split-K candidates
+]
+
+
+@pytest.mark.parametrize("T,dm,off,mask", MFMA_CASES)
+def test_bf16_mfma_path(mm, T, dm, off, mask):
+    args = small_bf16_case(T, T, dm, off, mask)
+    got = run_gpu(*args, path=mm.PATH_MFMA)
+    e_c, _ = check_bf16(got, args)
+    assert e_c < 4e-3          # same rounding contract: only accumulation order and rare one-ulp flips
+    again = run_gpu(*args, path=mm.PATH_MFMA)
+    assert np.array_equal(got, again)                      # bitwise reproducible
+
+
+DECODE_CASES = [
+    (1, 136, [0, 136, 136, 400, 520], [1, 1, 0, 1]),
+    (5, 264, [0, 8, 264, 272, 600], [1, 0, 1, 1]),
+    (16, 512, [0, 256, 512, 768], [1, 1, 1]),
+    (8, 64, [0, 24], [1]),
+    (16, 1096, [0, 1000, 2072], [1, 1]),                   # K tails in both kernels
+]
+
+
+@pytest.mark.parametrize("T,dm,off,mask", DECODE_CASES)
+def test_bf16_decode_path(mm, T, dm, off, mask):
+    args = small_bf16_case(100 + T, T, dm, off, mask)
+    got = run_gpu(*args, path=mm.PATH_DECODE)
+    e_c, _ = check_bf16(got, args)
+    assert e_c < 4e-3
+    assert np.array_equal(got, run_gpu(*args, path=mm.PATH_DECODE))
+    assert np.array_equal(got, run_gpu(*args))            # automatic choice for T <= 16
+
+
+def test_paths_agree_on_contract(mm):
+    """Generic, MFMA and decode kernels implement one rounding contract: they differ only by fp32 summation order."""
+    args = small_bf16_case(7, 16, 256, [0, 128, 256, 384], [1, 1, 1])
+    outs = [run_gpu(*args, path=p) for p in (mm.PATH_GENERIC, mm.PATH_MFMA, mm.PATH_DECODE)]
+    for o in outs[1:]:
+        assert oracle.rel_max_err(o, outs[0]) < 4e-3
+
+
+# ------------------------------------------------------------------ edge cases
+def test_edge_cases(mm):
+    import torch
+    args = list(small_bf16_case(3, 20, 64, [0, 64, 128], [1, 1]))
+    x, Wg, Wu, Wd, off, alpha, mask = args
+    dev = tuple(to_dev(a) for a in (x, Wg, Wu, Wd))
+    # nothing active: exact zeros on every path
+    none = np.zeros(2, np.uint8)
+    for p in (None, mm.PATH_GENERIC, mm.PATH_MFMA):
+        assert np.all(run_gpu(x, Wg, Wu, Wd, off, alpha, none, path=p, dev=dev) == 0)
+    # T == 0: accepted, nothing written
+    out = torch.zeros((0, 64), dtype=torch.float32, device="cuda")
+    mm.mlpmoe_forward_bf16(dev[0][:0], dev[1], dev[2], dev[3], off, alpha, mask, out=out)
+    # d_inter == 0 (one empty branch)
+    e_off = np.array([0, 0], np.int32)
+    got = run_gpu(x, Wg[:0], Wu[:0], np.ascontiguousarray(Wd[:, :0]), e_off, alpha[:1], mask[:1])
+    assert np.all(got == 0)
+    # non-finite weights inside a pruned branch must not leak, on any path
+    Wg2, Wu2, Wd2 = Wg.copy(), Wu.copy(), Wd.copy()
+    Wg2[64:] = 0x7FC0       # bf16 NaN
+    Wu2[64:] = 0x7F80       # +inf
+    Wd2[:, 64:] = 0x7FC0
+    m2 = np.array([1, 0], np.uint8)
+    ref = oracle_out(x, Wg, Wu, Wd, off, alpha, m2, "contract")
+    for p in (mm.PATH_GENERIC, mm.PATH_MFMA):
+        got = run_gpu(x, Wg2, Wu2, Wd2, off, alpha, m2, path=p)
+        assert np.all(np.isfinite(got)) and oracle.rel_max_err(got, ref) < 4e-3
+    got = run_gpu(x[:16], Wg2, Wu2, Wd2, off, alpha, m2, path=mm.PATH_DECODE)
+    assert np.all(np.isfinite(got)) and oracle.rel_max_err(got, ref[:16]) < 4e-3
+    # alpha == 0 with the mask set is computed (gives zeros on finite data), mask == 0 is skipped
+    a0 = alpha.copy()
+    a0[1] = 0
+    got_a0 = run_gpu(x, Wg, Wu, Wd, off, a0, mask, path=mm.PATH_MFMA, dev=dev)
+    assert oracle.rel_max_err(got_a0, ref) < 4e-3
+    # caller-owned workspace that is too small is refused
+    ws = torch.empty(256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(mm.MlpMoeError) as ei:
+        mm.mlpmoe_forward_bf16_ws(dev[0], dev[1], dev[2], dev[3], off, alpha, mask, ws)
+    assert ei.value.status == mm.ERR_WORKSPACE
+
+
+def test_max_branches_and_single_neuron_runs(mm):
+    """B = 64 with alternating pruned branches of 8 neurons: 32 separate runs."""
+    B = 64
+    off = (np.arange(B + 1) * 8).astype(np.int32)
+    mask = (np.arange(B) % 2 == 0).astype(np.uint8)
+    rng = np.random.default_rng(64)
+    x, Wg, Wu, Wd = synth.random_layer(rng, 33, 64, 512, dtype="bf16", w_scale=0.1)
+    alpha = rng.uniform(0.9, 1.2, size=B).astype(np.float32)
+    args = (x, Wg, Wu, Wd, off, alpha, mask)
+    for p in (mm.PATH_GENERIC, mm.PATH_MFMA):
+        check_bf16(run_gpu(*args, path=p), args)
+    a16 = (x[:16],) + args[1:]
+    check_bf16(run_gpu(*a16, path=mm.PATH_DECODE), a16)
+
+
+# ------------------------------------------------------------------ compaction (fade) end to end
+def test_slice_compact_forward_equals_zeroed_rows(mm):
+    """Neuron removal + compaction + padding on the device == the uncompacted layer with those
+    neurons' up-projection rows set to zero, evaluated by the oracle."""
+    L = synth.make_layer("llama8b_fade", 48, seed=2, d_model=128, d_inter=16 * 56)
+    B = L.workload.B
+    off, alpha1, mask, gather = mm.mlpmoe_slice(16 * 56, B, 0, L.neuron_keep, pad_to=8)
+    dev = tuple(to_dev(a) for a in (L.W_gate, L.W_up, L.W_down))
+    Wg_c, Wu_c, Wd_c = mm.mlpmoe_compact(dev[0], dev[1], dev[2], gather)
+    # data movement is bit exact against the oracle's gather
+    o_off, _, _, o_gather = oracle.slice_plan(16 * 56, B, 0, L.neuron_keep, 8)
+    rWg, rWu, rWd = oracle.compact_layer(L.W_gate, L.W_up, L.W_down, o_gather)
+    import torch
+    for t, r in ((Wg_c, rWg), (Wu_c, rWu), (Wd_c, rWd)):
+        assert np.array_equal(t.view(torch.int16).cpu().numpy().view(np.uint16), r)
+    alpha = L.alpha_draw
+    Wu_z = L.W_up.copy()
+    Wu_z[L.neuron_keep == 0] = 0
+    full_off = equal_offsets(16 * 56, B)
+    ref_args = (L.x, L.W_gate, Wu_z, L.W_down, full_off, alpha, mask)
+    x_d = to_dev(L.x)
+    for path in (mm.PATH_MFMA, mm.PATH_GENERIC):
+        ws = mm.new_workspace(48, 128, int(off[-1]), B)
+        out = mm.mlpmoe_forward_bf16_ws(x_d, Wg_c, Wu_c, Wd_c, off, alpha, mask, ws, path=path)
+        check_bf16(out.cpu().numpy(), ref_args)
+    # unpadded compaction has odd widths and takes the generic kernels
+    off1, _, _, gather1 = mm.mlpmoe_slice(16 * 56, B, 0, L.neuron_keep, pad_to=1)
+    c1 = mm.mlpmoe_compact(dev[0], dev[1], dev[2], gather1)
+    out = mm.mlpmoe_forward_bf16(x_d, c1[0], c1[1], c1[2], off1, alpha, mask)
+    check_bf16(out.cpu().numpy(), ref_args)
+
+
+def test_compensated_pruning_first_k(mm):
+    """Sec. 3.3 exactly: keep the first K of B branches with alpha = sqrt(B/K)."""
+    L = synth.make_layer("qwen05b", 40, seed=4, d_model=128, d_inter=8 * 64)
+    off, alpha, mask, _ = mm.mlpmoe_slice(8 * 64, 8, K_keep=6)
+    args = (L.x, L.W_gate, L.W_up, L.W_down, off, alpha, mask)
+    check_bf16(run_gpu(*args, path=mm.PATH_MFMA), args)
+    a16 = (L.x[:16],) + args[1:]
+    check_bf16(run_gpu(*a16, path=mm.PATH_DECODE), a16)

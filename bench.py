@@ -1,0 +1,213 @@
+#!/usr/bin/env python3
+"""Benchmark of the branched SwiGLU MLP forward (MLPMoE, Sec. 3.1) on one MI355X.
+
+A step is one call of the whole hot path (gate+up projection with the fused SiLU*up
+epilogue, down projection with the sum over branches) on one batch of T synthetic tokens
+that is already resident in HBM.  The headline workload is the Llama-8B-shaped layer
+(d_model 4096, d_inter 14336, B=16 branches of 896) at T=4096; the same layer is then timed
+at T=16 and T=1 through the decode kernels, rotating over several weight copies so that the
+weights come from HBM and not from the last-level cache.
+
+Prints ONE JSON line: tokens/s, the roofline of the dominant kernel (per-kernel durations come
+from HIP events the library records on the stream it launches on) and the CPU oracle timed on
+the host cores for context.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_PEAK_TFLOPS = 2516.6    # MI355X dense bf16: 256 CU x 2.4 GHz x 4096 flop/clk/CU
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="llama8b",
+                    choices=["qwen05b", "qwen05b_pruned", "llama8b", "llama8b_fade"])
+    ap.add_argument("--T", type=int, default=4096)
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    return ap.parse_args()
+
+
+def build_layer(mm, synth, name, T, seed):
+    """Synthetic layer -> device tensors + branch table (+ host copies for the oracle)."""
+    L = synth.make_layer(name, T, seed=seed)
+    w = L.workload
+    off, _, mask, gather = mm.mlpmoe_slice(w.d_inter, w.B, 0, L.neuron_keep, 8)
+    mask = mask.copy()
+    mask[L.inactive] = 0
+    alpha = L.alpha_draw
+    dev = [mm.bf16_tensor(a) for a in (L.W_gate, L.W_up, L.W_down)]
+    host = (L.W_gate, L.W_up, L.W_down)
+    d_eff_alg = int(sum(off[b + 1] - off[b] for b in range(w.B) if mask[b]))
+    if L.neuron_keep is not None:
+        dev = list(mm.mlpmoe_compact(dev[0], dev[1], dev[2], gather))
+        # algorithmic width counts kept neurons only, not the zero rows that pad branches to 8
+        kept = L.neuron_keep.reshape(w.B, -1).sum(axis=1)
+        d_eff_alg = int(sum(int(kept[b]) for b in range(w.B) if mask[b]))
+        import torch
+        host = tuple(t.view(torch.int16).cpu().numpy().view(np.uint16) for t in dev)
+    x = mm.bf16_tensor(L.x)
+    return L, x, dev, host, off, alpha, mask, d_eff_alg
+
+
+def time_steps(mm, torch, call, steps, warmup):
+    """Warm up, then time exactly `steps` calls; returns (ms_per_step, {kernel: [ms...]})."""
+    for i in range(warmup):
+        call(i)
+    torch.cuda.synchronize()
+    cap = steps * 4
+    mm.mlpmoe_profile_enable(cap)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        call(warmup + i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    per_kernel = {}
+    for name, ms in mm.mlpmoe_profile_collect(cap):
+        per_kernel.setdefault(name, []).append(ms)
+    mm.mlpmoe_profile_disable()
+    return (t1 - t0) * 1e3 / steps, per_kernel
+
+
+def roofline_of(per_kernel, T, d_model, d_eff, decode):
+    """Roofline of the kernel with the largest total time."""
+    if not per_kernel:
+        return None
+    dom = max(per_kernel, key=lambda k: sum(per_kernel[k]))
+    avg_ms = sum(per_kernel[dom]) / len(per_kernel[dom])
+    gate_up = "gate_up" in dom
+    if decode:
+        # weights of the kernel's projection(s) read once + activations in and out
+        wbytes = (2 if gate_up else 1) * d_model * d_eff * 2
+        io = T * d_model * 2 + T * d_eff * 2 if gate_up else T * d_eff * 2 + T * d_model * 4
+        ach = (wbytes + io) / (avg_ms * 1e-3) / 1e9
+        return {"kernel": dom, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,
+                "avg_kernel_us": round(avg_ms * 1e3, 2)}
+    flops = (4.0 if gate_up else 2.0) * T * d_model * d_eff
+    ach = flops / (avg_ms * 1e-3) / 1e12
+    return {"kernel": dom, "bound": "mfma", "achieved": round(ach, 1), "peak": MFMA_PEAK_TFLOPS,
+            "unit": "TFLOP/s", "frac": round(ach / MFMA_PEAK_TFLOPS, 4), "traffic": None,
+            "avg_kernel_us": round(avg_ms * 1e3, 2)}
+
+
+def cpu_baseline(synth, L, host, off, alpha, mask, seconds):
+    """The oracle as it stands (exact mode, OpenMP over tokens) on a bounded sample of the batch."""
+    import oracle
+    Wg, Wu, Wd = (synth.bf16_bits_to_f32(a) for a in host)
+    x = synth.bf16_bits_to_f32(L.x)
+    threads = oracle.num_threads()
+    n0 = min(L.T, threads)
+    t0 = time.perf_counter()
+    oracle.mlpmoe_forward(x[:n0], Wg, Wu, Wd, off, alpha, mask, mode="exact")
+    probe = time.perf_counter() - t0
+    n = int(max(n0, min(L.T, (seconds / max(probe, 1e-6)) * n0)))
+    n = max(threads, n // threads * threads) if L.T >= threads else L.T
+    n = min(n, L.T)
+    t0 = time.perf_counter()
+    oracle.mlpmoe_forward(x[:n], Wg, Wu, Wd, off, alpha, mask, mode="exact")
+    dt = time.perf_counter() - t0
+    return {"value": round(n / dt, 2), "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": "first %d of %d tokens of the same batch, exact fp64 mode, %.1f s" % (n, L.T, dt)}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (tokens are independent, so more GPUs would just "
+              "split the batch); --gpus %d is not supported." % args.gpus, file=sys.stderr)
+        return 2
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP library has no CPU fallback.", file=sys.stderr)
+        return 3
+    from paper_2511_21089_amd import binding as mm
+    from paper_2511_21089_amd import synth
+
+    L, x, dev, host, off, alpha, mask, d_eff = build_layer(mm, synth, args.workload, args.T, args.seed)
+    w = L.workload
+    T, d_model = args.T, w.d_model
+    decode = T <= 16
+    out = torch.empty((T, d_model), dtype=torch.float32, device="cuda")
+
+    # decode-sized batches cycle through copies of the weights so that every pass is cold
+    wbytes = 3 * d_model * int(off[-1]) * 2
+    n_sets = max(1, int(np.ceil(2 * 256e6 / wbytes))) if decode else 1
+    sets = [dev] + [[t.clone() for t in dev] for _ in range(n_sets - 1)]
+
+    def call(i):
+        Wg, Wu, Wd = sets[i % len(sets)]
+        mm.mlpmoe_forward_bf16(x, Wg, Wu, Wd, off, alpha, mask, out=out)
+
+    ms, per_kernel = time_steps(mm, torch, call, args.steps, args.warmup)
+    result = {
+        "metric": "MLP-layer tokens/s",
+        "value": round(T / (ms * 1e-3), 1),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s_T%d" % (args.workload, T), "d_model": d_model,
+                   "d_inter": w.d_inter, "B": w.B, "d_eff": d_eff, "T": T,
+                   "active_branches": int(mask.sum()), "weight_sets": len(sets)},
+        "roofline": roofline_of(per_kernel, T, d_model, d_eff, decode),
+        "kernels_us": {k: round(1e3 * sum(v) / len(v), 2) for k, v in per_kernel.items()},
+    }
+    flops = 6.0 * T * d_model * d_eff
+    result["whole_path"] = {
+        "tflops": round(flops / (ms * 1e-3) / 1e12, 1),
+        "mfma_frac": round(flops / (ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS, 4),
+        "gbs": round((3 * d_model * d_eff * 2 + T * d_model * 6) / (ms * 1e-3) / 1e9, 1),
+    }
+    result["whole_path"]["hbm_frac"] = round(result["whole_path"]["gbs"] / HBM_PEAK_GBS, 4)
+
+    if not decode and not args.no_decode:
+        # the second half of the metric: the same layer through the decode kernels
+        n_sets = max(2, int(np.ceil(2 * 256e6 / wbytes)))
+        sets = [dev] + [[t.clone() for t in dev] for _ in range(n_sets - 1)]
+        dec = {}
+        for Td in (16, 1):
+            xd = x[:Td].contiguous()
+            outd = torch.empty((Td, d_model), dtype=torch.float32, device="cuda")
+
+            def calld(i, xd=xd, outd=outd):
+                Wg, Wu, Wd = sets[i % len(sets)]
+                mm.mlpmoe_forward_bf16(xd, Wg, Wu, Wd, off, alpha, mask, out=outd)
+
+            msd, pk = time_steps(mm, torch, calld, 50, 10)
+            byts = 3 * d_model * d_eff * 2 + Td * d_model * 6
+            dec["T%d" % Td] = {"tokens_per_s": round(Td / (msd * 1e-3), 1), "us_per_step": round(msd * 1e3, 2),
+                               "gbs": round(byts / (msd * 1e-3) / 1e9, 1),
+                               "hbm_frac": round(byts / (msd * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                               "roofline": roofline_of(pk, Td, d_model, d_eff, True),
+                               "kernels_us": {k: round(1e3 * sum(v) / len(v), 2) for k, v in pk.items()}}
+        dec["weight_sets"] = len(sets)
+        result["decode"] = dec
+        del sets
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(synth, L, host, off, alpha, mask, args.cpu_seconds)
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

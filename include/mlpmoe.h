@@ -183,6 +183,33 @@ MLPMOE_API int mlpmoe_forward_f32_ws(const float *x, const float *W_gate, const 
                           const uint8_t *active_mask, int T, int d_model, int d_inter, int B,
                           float *out, void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Per-kernel timing (measurement aid; the arithmetic is unchanged and nothing is skipped).
+ * While enabled, every kernel a forward call launches is bracketed by a pair of HIP events
+ * recorded on the call's own stream.
+ *   mlpmoe_profile_enable(capacity)  creates 2*capacity events on the current device and
+ *                                    starts recording; capacity in [1, 65536].
+ *   mlpmoe_profile_collect(ids, ms, capacity)  waits for the recorded events, writes up to
+ *       capacity records in launch order (ids[i] = MLPMOE_KERNEL_*, ms[i] = duration in
+ *       milliseconds), clears the record list and returns the number written (>= 0), or a
+ *       negative error.  Launches beyond the enabled capacity are not recorded.
+ *   mlpmoe_profile_disable()         stops recording and destroys the events.
+ * Not thread safe; intended for one benchmarking thread.
+ */
+enum {
+    MLPMOE_KERNEL_GATE_UP_MFMA = 1,
+    MLPMOE_KERNEL_DOWN_MFMA = 2,
+    MLPMOE_KERNEL_SPLITK_REDUCE = 3,
+    MLPMOE_KERNEL_DECODE_GATE_UP = 4,
+    MLPMOE_KERNEL_DECODE_DOWN = 5,
+    MLPMOE_KERNEL_GATE_UP_GENERIC = 6,
+    MLPMOE_KERNEL_DOWN_GENERIC = 7,
+    MLPMOE_KERNEL_FILL_ZERO = 8
+};
+MLPMOE_API int mlpmoe_profile_enable(int capacity);
+MLPMOE_API int mlpmoe_profile_collect(int *ids, float *ms, int capacity);
+MLPMOE_API int mlpmoe_profile_disable(void);
+
 /* Frees the library-owned per-device workspaces (synchronises each device first). */
 MLPMOE_API int mlpmoe_release(void);
 

@@ -24,7 +24,8 @@ MAX_BRANCHES = 64
 
 EXPORTS = ["mlpmoe_status_string", "mlpmoe_slice", "mlpmoe_compact", "mlpmoe_workspace_bytes",
            "mlpmoe_forward_bf16", "mlpmoe_forward", "mlpmoe_forward_f32", "mlpmoe_forward_bf16_ws",
-           "mlpmoe_forward_f32_ws", "mlpmoe_release"]
+           "mlpmoe_forward_f32_ws", "mlpmoe_release", "mlpmoe_profile_enable",
+           "mlpmoe_profile_collect", "mlpmoe_profile_disable"]
 
 
 class MlpMoeError(RuntimeError):
@@ -58,6 +59,12 @@ def _load() -> ctypes.CDLL:
     lib.mlpmoe_forward_f32_ws.restype = i
     lib.mlpmoe_release.argtypes = []
     lib.mlpmoe_release.restype = i
+    lib.mlpmoe_profile_enable.argtypes = [i]
+    lib.mlpmoe_profile_enable.restype = i
+    lib.mlpmoe_profile_collect.argtypes = [vp, vp, i]
+    lib.mlpmoe_profile_collect.restype = i
+    lib.mlpmoe_profile_disable.argtypes = []
+    lib.mlpmoe_profile_disable.restype = i
     return lib
 
 
@@ -187,6 +194,28 @@ def mlpmoe_forward_f32_ws(x, W_gate, W_up, W_down, branch_offsets, alpha, active
 
 def mlpmoe_release():
     _check(lib.mlpmoe_release(), "mlpmoe_release")
+
+
+KERNEL_NAMES = {1: "gate_up_mfma", 2: "down_mfma", 3: "splitk_reduce", 4: "decode_gate_up",
+                5: "decode_down", 6: "gate_up_generic", 7: "down_generic", 8: "fill_zero"}
+
+
+def mlpmoe_profile_enable(capacity: int):
+    _check(lib.mlpmoe_profile_enable(int(capacity)), "mlpmoe_profile_enable")
+
+
+def mlpmoe_profile_collect(capacity: int):
+    """Returns [(kernel_name, milliseconds), ...] in launch order and clears the record list."""
+    ids = np.zeros(capacity, dtype=np.int32)
+    ms = np.zeros(capacity, dtype=np.float32)
+    n = lib.mlpmoe_profile_collect(ids.ctypes.data, ms.ctypes.data, int(capacity))
+    if n < 0:
+        raise MlpMoeError(n, "mlpmoe_profile_collect")
+    return [(KERNEL_NAMES.get(int(ids[k]), str(ids[k])), float(ms[k])) for k in range(n)]
+
+
+def mlpmoe_profile_disable():
+    _check(lib.mlpmoe_profile_disable(), "mlpmoe_profile_disable")
 
 
 def new_workspace(T, d_model, d_inter, B, elem_bytes=2, device="cuda"):

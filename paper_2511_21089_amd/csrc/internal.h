@@ -55,4 +55,14 @@ hipError_t launch_compact(const void *Wg, const void *Wu, const void *Wd, const 
                           int n_rows, int d_model, int d_inter_src, int elem_bytes, void *Wg_c,
                           void *Wu_c, void *Wd_c, hipStream_t s);
 
+
+// Brackets one kernel launch with a pair of events when profiling is enabled.
+void profile_mark(int kernel_id, hipStream_t s, bool begin);
+struct ProfileScope {
+    int id;
+    hipStream_t s;
+    ProfileScope(int kernel_id, hipStream_t stream) : id(kernel_id), s(stream) { profile_mark(id, s, true); }
+    ~ProfileScope() { profile_mark(id, s, false); }
+};
+
 }  // namespace mlpmoe

@@ -152,9 +152,13 @@ hipError_t launch_decode_bf16(const FwdArgs &a, const BranchTable &bt)
     if (tiles1 > 0x7fffffffLL) return hipErrorInvalidValue;
     const uint16_t *X = static_cast<const uint16_t *>(a.x);
     uint16_t *H = static_cast<uint16_t *>(a.H);
+    {
+    ProfileScope ps(MLPMOE_KERNEL_DECODE_GATE_UP, a.stream);
     decode_kernel<4, true><<<(unsigned)tiles1, 256, 0, a.stream>>>(
         X, a.d_model, a.T, static_cast<const uint16_t *>(a.Wg), static_cast<const uint16_t *>(a.Wu),
         a.d_model, a.d_model, H, a.ldh, nullptr, bt);
+    }
+    ProfileScope ps(MLPMOE_KERNEL_DECODE_DOWN, a.stream);
     if (tiles2 >= 192)
         decode_kernel<8, false><<<tiles2, 512, 0, a.stream>>>(
             H, a.ldh, a.T, static_cast<const uint16_t *>(a.Wd), nullptr, a.d_inter, a.d_model, nullptr,

@@ -224,9 +224,13 @@ hipError_t launch_generic_typed(const FwdArgs &a, const BranchTable &bt)
     dim3 g1(ceil_div(a.d_inter, GT), ceil_div(a.T, GT));
     dim3 g2(ceil_div(a.d_model, GT), ceil_div(a.T, GT));
     if (g1.y > 65535u || g2.y > 65535u) return hipErrorInvalidValue;
+    {
+    ProfileScope ps(MLPMOE_KERNEL_GATE_UP_GENERIC, a.stream);
     gate_up_generic<TIn, TH><<<g1, GTHREADS, 0, a.stream>>>(
         static_cast<const TIn *>(a.x), static_cast<const TIn *>(a.Wg), static_cast<const TIn *>(a.Wu),
         static_cast<TH *>(a.H), a.T, a.d_model, a.d_inter, a.ldh, bt);
+    }
+    ProfileScope ps(MLPMOE_KERNEL_DOWN_GENERIC, a.stream);
     down_generic<TIn, TH><<<g2, GTHREADS, 0, a.stream>>>(
         static_cast<const TH *>(a.H), static_cast<const TIn *>(a.Wd), a.out, a.T, a.d_model, a.d_inter,
         a.ldh, bt);
@@ -240,6 +244,7 @@ hipError_t launch_fill_zero(float *out, size_t n, hipStream_t s)
     if (n == 0) return hipSuccess;
     size_t blocks = (n + 255) / 256;
     if (blocks > 4096) blocks = 4096;
+    ProfileScope ps(MLPMOE_KERNEL_FILL_ZERO, s);
     fill_zero_kernel<<<(unsigned)blocks, 256, 0, s>>>(out, n);
     return hipGetLastError();
 }

@@ -368,15 +368,22 @@ hipError_t launch_mfma_bf16(const FwdArgs &a, const BranchTable &bt)
     const long long grid2 = (long long)tiles_m * tiles_n2 * splits;
     if (grid1 > 0x7fffffffLL || grid2 > 0x7fffffffLL) return hipErrorInvalidValue;
 
+    {
+    ProfileScope ps(MLPMOE_KERNEL_GATE_UP_MFMA, a.stream);
     gate_up_mfma<<<(unsigned)grid1, THREADS, 0, a.stream>>>(
         static_cast<const uint16_t *>(a.x), static_cast<const uint16_t *>(a.Wg),
         static_cast<const uint16_t *>(a.Wu), static_cast<uint16_t *>(a.H), a.T, a.d_model, a.d_inter,
         a.ldh, tiles_m, bt);
+    }
     float *dst = splits > 1 ? a.partial : a.out;
+    {
+    ProfileScope ps(MLPMOE_KERNEL_DOWN_MFMA, a.stream);
     down_mfma<<<(unsigned)grid2, THREADS, 0, a.stream>>>(
         static_cast<const uint16_t *>(a.H), static_cast<const uint16_t *>(a.Wd), dst, a.T, a.d_model,
         a.d_inter, a.ldh, tiles_m, tiles_n2, splits, kt_total, bt);
+    }
     if (splits > 1) {
+        ProfileScope ps(MLPMOE_KERNEL_SPLITK_REDUCE, a.stream);
         const size_t n = (size_t)a.T * a.d_model;
         size_t blocks = (n + 255) / 256;
         if (blocks > 8192) blocks = 8192;

@@ -6,6 +6,7 @@
 
 #include <map>
 #include <mutex>
+#include <vector>
 
 #include "internal.h"
 
@@ -19,6 +20,14 @@ struct DeviceWorkspace {
 };
 std::mutex g_ws_mutex;
 std::map<int, DeviceWorkspace> g_ws;
+
+// --- per-kernel event timing -------------------------------------------------
+struct Profiler {
+    bool on = false;
+    int capacity = 0, count = 0;
+    std::vector<hipEvent_t> ev;      // 2 per record: begin, end
+    std::vector<int> ids;
+} g_prof;
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -93,6 +102,9 @@ int forward_impl(const void *x, const void *Wg, const void *Wu, const void *Wd, 
 
     BranchTable bt;
     build_table(off, alpha, mask, B, bt);
+    // launch status is read back with hipGetLastError(): drop whatever an earlier, unrelated
+    // runtime call of this thread left behind (e.g. a "not ready" from an event query)
+    (void)hipGetLastError();
 
     if (bt.n_runs == 0) {   // nothing active: the sum over branches is empty
         return launch_fill_zero(out, (size_t)T * d_model, stream) == hipSuccess ? MLPMOE_OK
@@ -173,7 +185,62 @@ int forward_owned(const void *x, const void *Wg, const void *Wu, const void *Wd,
 
 }  // namespace
 
+namespace mlpmoe {
+void profile_mark(int kernel_id, hipStream_t s, bool begin)
+{
+    if (!g_prof.on) return;
+    if (begin) {
+        if (g_prof.count >= g_prof.capacity) return;
+        g_prof.ids[g_prof.count] = kernel_id;
+        (void)hipEventRecord(g_prof.ev[2 * g_prof.count], s);
+    } else {
+        if (g_prof.count >= g_prof.capacity) return;
+        (void)hipEventRecord(g_prof.ev[2 * g_prof.count + 1], s);
+        ++g_prof.count;
+    }
+}
+}  // namespace mlpmoe
+
 extern "C" {
+
+int mlpmoe_profile_disable(void)
+{
+    for (hipEvent_t e : g_prof.ev) (void)hipEventDestroy(e);
+    g_prof = Profiler();
+    return MLPMOE_OK;
+}
+
+int mlpmoe_profile_enable(int capacity)
+{
+    if (capacity < 1 || capacity > 65536) return MLPMOE_ERR_SHAPE;
+    mlpmoe_profile_disable();
+    g_prof.ev.resize(2 * (size_t)capacity);
+    g_prof.ids.assign(capacity, 0);
+    for (size_t i = 0; i < g_prof.ev.size(); ++i)
+        if (hipEventCreate(&g_prof.ev[i]) != hipSuccess) {
+            g_prof.ev.resize(i);
+            mlpmoe_profile_disable();
+            return MLPMOE_ERR_HIP;
+        }
+    g_prof.capacity = capacity;
+    g_prof.on = true;
+    return MLPMOE_OK;
+}
+
+int mlpmoe_profile_collect(int *ids, float *ms, int capacity)
+{
+    if (!ids || !ms) return MLPMOE_ERR_NULL;
+    if (capacity < 0) return MLPMOE_ERR_SHAPE;
+    int n = g_prof.count < capacity ? g_prof.count : capacity;
+    for (int i = 0; i < n; ++i) {
+        if (hipEventSynchronize(g_prof.ev[2 * i + 1]) != hipSuccess ||
+            hipEventElapsedTime(&ms[i], g_prof.ev[2 * i], g_prof.ev[2 * i + 1]) != hipSuccess)
+            return MLPMOE_ERR_HIP;
+        ids[i] = g_prof.ids[i];
+    }
+    g_prof.count = 0;
+    return n;
+}
 
 const char *mlpmoe_status_string(int status)
 {
@@ -245,6 +312,7 @@ int mlpmoe_compact(const void *W_gate, const void *W_up, const void *W_down, con
     if (n_rows == 0) return MLPMOE_OK;
     if (!W_gate || !W_up || !W_down || !gather || !W_gate_c || !W_up_c || !W_down_c)
         return MLPMOE_ERR_NULL;
+    (void)hipGetLastError();
     hipError_t e = launch_compact(W_gate, W_up, W_down, gather, n_rows, d_model, d_inter_src,
                                   elem_bytes, W_gate_c, W_up_c, W_down_c,
                                   static_cast<hipStream_t>(stream));

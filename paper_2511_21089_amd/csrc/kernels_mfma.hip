@@ -22,16 +22,25 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 constexpr int BM = 256;          // tokens per tile
 constexpr int BNH = 128;         // rows of each of the two B blocks
-constexpr int BK = 64;           // K elements per stage
+constexpr int BK = 64;           // K elements per stage: one tile row is 128 bytes = 8 chunks of 16
 constexpr int THREADS = 256;
-constexpr int LDS_ROW = BK + 8;  // padded row (elements): 144 B keeps ds_read_b128 conflict free
-constexpr int STAGE_ELEMS = (BM + 2 * BNH) * LDS_ROW;
-constexpr int A_CHUNKS = BM * (BK / 8) / THREADS;    // 16-byte chunks per thread: 8
-constexpr int B_CHUNKS = BNH * (BK / 8) / THREADS;   // 4 per block
+constexpr int A_BYTES = BM * BK * 2;                 // 32768
+constexpr int B_BYTES = BNH * BK * 2;                // 16384
+constexpr int STAGE_BYTES = A_BYTES + 2 * B_BYTES;   // 65536
+constexpr int A_LOADS = A_BYTES / 1024 / 4;          // 1 KiB wave-loads per wave: 8
+constexpr int B_LOADS = B_BYTES / 1024 / 4;          // 4 per block
 
-struct TileRegs {
-    u32x4 a[A_CHUNKS], b0[B_CHUNKS], b1[B_CHUNKS];
-};
+// 16 zero bytes: K chunks that fall past the end of a range are fetched from here.
+__device__ const uint32_t g_zero_chunk[4] = {0, 0, 0, 0};
+
+typedef const __attribute__((address_space(1))) void *gptr_t;
+typedef __attribute__((address_space(3))) void *lptr_t;
+
+// One wave-wide 16-byte-per-lane load straight into LDS: lane l's data lands at dst + 16*l.
+__device__ __forceinline__ void dma16(const void *src, void *lds_dst)
+{
+    __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)lds_dst, 16, 0, 0);
+}
 
 // Position in the flattened list of K tiles (ranges laid end to end).
 struct KCursor {
@@ -70,127 +79,148 @@ __device__ __forceinline__ KCursor k_seek(const KR &kr, int tile)
     return c;
 }
 
-__device__ __forceinline__ u32x4 ld16(const uint16_t *p) { return *reinterpret_cast<const u32x4 *>(p); }
-
-// Main loop.  A: [*, lda] rows a_row0.. (clamped to a_rows-1), B0/B1: [*, ldb] rows.
-// K tiles [kt_begin, kt_end) of the flattened range list kr.
-// Rows outside the valid range are clamped to a valid row: their results are never stored,
-// and MFMA rows/columns do not mix.  K chunks outside a run are zero in A and in B.
+// LDS tile layout.  A stage holds A (256 rows), B0 (128 rows), B1 (128 rows), each row 128 bytes
+// = 8 chunks of 8 bf16.  Chunk c of row r is stored at chunk slot c ^ swz(r),
+// swz(r) = (r & 7) ^ ((r >> 3) & 1), so that the 16-byte reads of 32 consecutive rows at one
+// logical chunk fall on distinct banks.  Direct-to-LDS loads write 1 KiB = 8 whole rows per wave
+// instruction, so the swizzle is applied on the global side: the lane that fills slot p of row r
+// fetches logical chunk p ^ swz(r).
+//
+// Main loop.  A_tile / B0_tile / B1_tile point at the first row of the tile (wave uniform);
+// a_valid / b0_valid / b1_valid are the rows that exist from there on (>= 1).  Rows past that
+// are clamped to the last valid row: their results are never stored and MFMA rows / columns do
+// not mix.  K chunks past the end of a range are read from a zero chunk, in A and in B.
+// Pipeline: two LDS stages; the loads of tile i+1 are issued at the top of iteration i and
+// waited for at the barrier that sits before the last K step, so that the first fragments of
+// tile i+1 are read while the last MFMAs of tile i run.  Fragments are double buffered in
+// registers one K step ahead.
 template <typename KR>
-__device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A, int lda, int a_row0, int a_rows,
-                                         const uint16_t *__restrict__ B0, const uint16_t *__restrict__ B1,
-                                         int ldb, int b0_row0, int b1_row0, int b_rows,
-                                         const KR &kr, int kt_begin, int kt_end,
-                                         uint16_t *lds, f32x16 (&acc0)[4][2], f32x16 (&acc1)[4][2])
+__device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, int lda, int a_valid,
+                                         const uint16_t *__restrict__ B0_tile,
+                                         const uint16_t *__restrict__ B1_tile, int ldb, int b0_valid,
+                                         int b1_valid, const KR &kr, int kt_begin, int kt_end, char *lds,
+                                         f32x16 (&acc0)[4][2], f32x16 (&acc1)[4][2])
 {
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
-    const int kc = tid & 7;                  // 16-byte chunk inside the 128-byte tile row
-    const int r_in = tid >> 3;               // 0..31: row inside a 32-row slab
-
-    const uint16_t *a_ptr[A_CHUNKS];
-    const uint16_t *b0_ptr[B_CHUNKS], *b1_ptr[B_CHUNKS];
-#pragma unroll
-    for (int i = 0; i < A_CHUNKS; ++i) {
-        int r = a_row0 + i * 32 + r_in;
-        r = r < a_rows ? r : a_rows - 1;
-        a_ptr[i] = A + (size_t)r * lda + kc * 8;
-    }
-#pragma unroll
-    for (int i = 0; i < B_CHUNKS; ++i) {
-        int r0 = b0_row0 + i * 32 + r_in, r1 = b1_row0 + i * 32 + r_in;
-        r0 = r0 < b_rows ? r0 : b_rows - 1;
-        r1 = r1 < b_rows ? r1 : b_rows - 1;
-        b0_ptr[i] = B0 + (size_t)r0 * ldb + kc * 8;
-        b1_ptr[i] = B1 + (size_t)r1 * ldb + kc * 8;
-    }
-
-    auto load_tile = [&](const KCursor &c, TileRegs &t) {
-        if (c.k + BK <= kr.end(c.run)) {     // whole tile inside the range (uniform branch)
-#pragma unroll
-            for (int i = 0; i < A_CHUNKS; ++i) t.a[i] = ld16(a_ptr[i] + c.k);
-#pragma unroll
-            for (int i = 0; i < B_CHUNKS; ++i) {
-                t.b0[i] = ld16(b0_ptr[i] + c.k);
-                t.b1[i] = ld16(b1_ptr[i] + c.k);
-            }
-        } else {                             // last tile of a range: chunks past its end are zero
-            const bool ok = c.k + kc * 8 < kr.end(c.run);
-            const u32x4 z = {0, 0, 0, 0};
-#pragma unroll
-            for (int i = 0; i < A_CHUNKS; ++i) t.a[i] = ok ? ld16(a_ptr[i] + c.k) : z;
-#pragma unroll
-            for (int i = 0; i < B_CHUNKS; ++i) {
-                t.b0[i] = ok ? ld16(b0_ptr[i] + c.k) : z;
-                t.b1[i] = ok ? ld16(b1_ptr[i] + c.k) : z;
-            }
-        }
-    };
-    auto store_tile = [&](const TileRegs &t, uint16_t *stage) {
-        uint16_t *sa = stage, *sb0 = stage + BM * LDS_ROW, *sb1 = sb0 + BNH * LDS_ROW;
-#pragma unroll
-        for (int i = 0; i < A_CHUNKS; ++i)
-            *reinterpret_cast<u32x4 *>(sa + (i * 32 + r_in) * LDS_ROW + kc * 8) = t.a[i];
-#pragma unroll
-        for (int i = 0; i < B_CHUNKS; ++i) {
-            *reinterpret_cast<u32x4 *>(sb0 + (i * 32 + r_in) * LDS_ROW + kc * 8) = t.b0[i];
-            *reinterpret_cast<u32x4 *>(sb1 + (i * 32 + r_in) * LDS_ROW + kc * 8) = t.b1[i];
-        }
-    };
-    auto advance = [&](KCursor &c) {
-        c.k += BK;
-        if (c.k >= kr.end(c.run)) {
-            ++c.run;
-            c.k = c.run < kr.n_runs() ? kr.start(c.run) : 0;
-        }
-    };
-
     const int nk = kt_end - kt_begin;
     if (nk <= 0) return;
-    KCursor cur = k_seek(kr, kt_begin);
-    TileRegs regs;
-    load_tile(cur, regs);
-    store_tile(regs, lds);
-    __syncthreads();
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
 
-    // per-lane read offsets inside a stage (elements)
-    const int lrow = lane & 31, lk = (lane >> 5) * 8;
-    const int a_off = (wm * 128 + lrow) * LDS_ROW + lk;
-    const int b_off = (wn * 64 + lrow) * LDS_ROW + lk;
+    // ---- global side: per-lane byte offsets of this wave's loads, relative to the tile pointers
+    const int lr = lane >> 3;                     // row inside the 8-row slab of one wave-load
+    const int cs[2] = {(lane & 7) ^ lr, (lane & 7) ^ lr ^ 1};   // logical chunk for even / odd slabs
+    unsigned a_off[A_LOADS], b0_off[B_LOADS], b1_off[B_LOADS];
+#pragma unroll
+    for (int i = 0; i < A_LOADS; ++i) {
+        int r = (wave * A_LOADS + i) * 8 + lr;
+        r = r < a_valid ? r : a_valid - 1;
+        a_off[i] = (unsigned)r * (unsigned)lda * 2u + (unsigned)cs[i & 1] * 16u;
+    }
+#pragma unroll
+    for (int i = 0; i < B_LOADS; ++i) {
+        const int r = (wave * B_LOADS + i) * 8 + lr;
+        const int r0 = r < b0_valid ? r : b0_valid - 1;
+        const int r1 = r < b1_valid ? r : b1_valid - 1;
+        b0_off[i] = (unsigned)r0 * (unsigned)ldb * 2u + (unsigned)cs[i & 1] * 16u;
+        b1_off[i] = (unsigned)r1 * (unsigned)ldb * 2u + (unsigned)cs[i & 1] * 16u;
+    }
+    const char *a_base = reinterpret_cast<const char *>(A_tile);
+    const char *b0_base = reinterpret_cast<const char *>(B0_tile);
+    const char *b1_base = reinterpret_cast<const char *>(B1_tile);
+    char *a_dst = lds + wave * (A_LOADS * 1024);
+    char *b0_dst = lds + A_BYTES + wave * (B_LOADS * 1024);
+    char *b1_dst = b0_dst + B_BYTES;
+
+    // Direct load number n (0..15) of the next tile: 0-7 A slabs, 8-11 B0, 12-15 B1.  Branch free
+    // on purpose, so that the loads sit in the same basic block as the MFMAs; a lane whose chunk
+    // lies past the end of the range (or with no tile left: kend very negative) reads the zero chunk.
+    const char *zero = reinterpret_cast<const char *>(g_zero_chunk);
+    auto dma_n = [&](int n, int k, int kend, int stage) {
+        const int so = stage * STAGE_BYTES;
+        const size_t kb = (size_t)k * 2;
+        const bool ok = k + cs[n & 1] * 8 < kend;
+        if (n < 8) dma16(ok ? a_base + kb + a_off[n] : zero, a_dst + so + n * 1024);
+        else if (n < 12) dma16(ok ? b0_base + kb + b0_off[n - 8] : zero, b0_dst + so + (n - 8) * 1024);
+        else dma16(ok ? b1_base + kb + b1_off[n - 12] : zero, b1_dst + so + (n - 12) * 1024);
+    };
+    auto advance = [&](KCursor &c) {      // stays on the last range once the list is exhausted
+        c.k += BK;
+        if (c.k >= kr.end(c.run) && c.run + 1 < kr.n_runs()) {
+            ++c.run;
+            c.k = kr.start(c.run);
+        }
+    };
+
+    // ---- LDS side: per-lane read offsets (bytes) for the 4 K steps of a stage
+    const int lrow = lane & 31;
+    const int swz = (lane & 7) ^ ((lane >> 3) & 1);          // tile rows start at multiples of 32
+    int a_rd[BK / 16], b_rd[BK / 16];
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+        const int slot = (ks * 2 + (lane >> 5)) ^ swz;
+        a_rd[ks] = (wm * 128 + lrow) * 128 + slot * 16;
+        b_rd[ks] = A_BYTES + (wn * 64 + lrow) * 128 + slot * 16;
+    }
+    // Fragment pieces of one K step in the order they are read: the four B pieces first
+    // (b0[0], b1[0], b0[1], b1[1]), then a[0..3].  MFMA m uses a[m >> 2] and B piece m & 3, so the
+    // piece that is read last (a[3]) is needed only by the last four MFMAs of the following step.
+    struct Frags {
+        bf16x8 v[8];
+    };
+    auto read_piece = [&](Frags &f, int g, int stage, int ks) {
+        const char *s = lds + stage * STAGE_BYTES;
+        if (g < 4) f.v[g] = *reinterpret_cast<const bf16x8 *>(s + b_rd[ks] + (g & 1) * B_BYTES + (g >> 1) * 4096);
+        else f.v[g] = *reinterpret_cast<const bf16x8 *>(s + a_rd[ks] + (g - 4) * 4096);
+    };
+    auto mfma_n = [&](const Frags &f, int m) {
+        const int i = m >> 2, j = (m >> 1) & 1;
+        if (m & 1) acc1[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.v[4 + i], f.v[m & 3], acc1[i][j], 0, 0, 0);
+        else acc0[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.v[4 + i], f.v[m & 3], acc0[i][j], 0, 0, 0);
+    };
+    // One K step, written in the instruction order wanted: 8 slots of {2 MFMAs, then LDS reads of
+    // the next step's fragments, then one direct load of the next tile (optional)}; nothing may be
+    // moved across a slot boundary.  The compiler waits for ALL outstanding LDS reads before the
+    // first MFMA of a step (direct-to-LDS loads in flight make it give up exact counting), so the
+    // eight reads are packed into slots 0-5 and the last two slots leave them time to land.
+    auto k_step = [&](const Frags &cur_f, Frags &nxt_f, int rd_stage, int rd_ks, int dma_first, int k,
+                      int kend, int dma_stage) {
+#pragma unroll
+        for (int g = 0; g < 8; ++g) {
+            mfma_n(cur_f, 2 * g);
+            mfma_n(cur_f, 2 * g + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            if (g < 2) {
+                read_piece(nxt_f, 2 * g, rd_stage, rd_ks);
+                read_piece(nxt_f, 2 * g + 1, rd_stage, rd_ks);
+            } else if (g < 6) {
+                read_piece(nxt_f, g + 2, rd_stage, rd_ks);
+            }
+            if (dma_first >= 0) dma_n(dma_first + g, k, kend, dma_stage);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    KCursor cur = k_seek(kr, kt_begin);
+#pragma unroll
+    for (int n = 0; n < 16; ++n) dma_n(n, cur.k, kr.end(cur.run), 0);
+    __syncthreads();
+    Frags f0, f1;
+#pragma unroll
+    for (int g = 0; g < 8; ++g) read_piece(f0, g, 0, 0);
 
     for (int it = 0; it < nk; ++it) {
-        uint16_t *stage = lds + (it & 1) * STAGE_ELEMS;
-        const bool more = it + 1 < nk;
-        if (more) {
-            advance(cur);
-            load_tile(cur, regs);
-        }
-        const uint16_t *sa = stage + a_off;
-        const uint16_t *sb0 = stage + BM * LDS_ROW + b_off;
-        const uint16_t *sb1 = sb0 + BNH * LDS_ROW;
-#pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8 af[4], bf0[2], bf1[2];
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                af[i] = *reinterpret_cast<const bf16x8 *>(sa + i * 32 * LDS_ROW + ks * 16);
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                bf0[j] = *reinterpret_cast<const bf16x8 *>(sb0 + j * 32 * LDS_ROW + ks * 16);
-                bf1[j] = *reinterpret_cast<const bf16x8 *>(sb1 + j * 32 * LDS_ROW + ks * 16);
-            }
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    acc0[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf0[j], acc0[i][j], 0, 0, 0);
-                    acc1[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf1[j], acc1[i][j], 0, 0, 0);
-                }
-        }
-        if (more) store_tile(regs, lds + ((it + 1) & 1) * STAGE_ELEMS);
-        __syncthreads();
+        const int st = it & 1;
+        advance(cur);
+        const int kend = it + 1 < nk ? kr.end(cur.run) : -(1 << 30);
+        k_step(f0, f1, st, 1, 0, cur.k, kend, st ^ 1);
+        k_step(f1, f0, st, 2, 8, cur.k, kend, st ^ 1);
+        k_step(f0, f1, st, 3, -1, 0, 0, 0);
+        __syncthreads();                          // tile it+1 has landed; stage st is free again
+        k_step(f1, f0, st ^ 1, 0, -1, 0, 0, 0);   // (after the last tile this reads zeros, unused)
     }
+    __syncthreads();                              // LDS may be reused by the caller
 }
 
 __device__ __forceinline__ int branch_of(const BranchTable &bt, int j)
@@ -219,7 +249,7 @@ gate_up_mfma(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
              const uint16_t *__restrict__ Wu, uint16_t *__restrict__ H, int T, int d_model, int d_inter,
              int ldh, int tiles_m, BranchTable bt)
 {
-    __shared__ __attribute__((aligned(16))) uint16_t lds[2 * STAGE_ELEMS];
+    __shared__ __attribute__((aligned(1024))) char lds[2 * STAGE_BYTES];
     const int tm = blockIdx.x % tiles_m;
     int tn = blockIdx.x / tiles_m;
     int n0 = 0, n_end = 0;
@@ -247,7 +277,9 @@ gate_up_mfma(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
             }
 
     const int nk = (d_model + BK - 1) / BK;
-    mainloop(X, d_model, t0, T, Wg, Wu, d_model, n0, n0, n_end, KSingle{d_model}, 0, nk, lds, accg, accu);
+    mainloop(X + (size_t)t0 * d_model, d_model, T - t0, Wg + (size_t)n0 * d_model,
+             Wu + (size_t)n0 * d_model, d_model, n_end - n0, n_end - n0, KSingle{d_model}, 0, nk, lds,
+             accg, accu);
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -273,7 +305,7 @@ down_mfma(const uint16_t *__restrict__ H, const uint16_t *__restrict__ Wd, float
           int d_model, int d_inter, int ldh, int tiles_m, int tiles_n, int splits, int kt_total,
           BranchTable bt)
 {
-    __shared__ __attribute__((aligned(16))) uint16_t lds[2 * STAGE_ELEMS];
+    __shared__ __attribute__((aligned(1024))) char lds[2 * STAGE_BYTES];
     int id = blockIdx.x;
     const int tm = id % tiles_m;
     id /= tiles_m;
@@ -294,8 +326,10 @@ down_mfma(const uint16_t *__restrict__ H, const uint16_t *__restrict__ Wd, float
                 acc1[i][j][v] = 0.f;
             }
 
-    mainloop(H, ldh, t0, T, Wd, Wd, d_inter, n0, n0 + BNH, d_model, KRuns{bt}, kt_begin, kt_end, lds,
-             acc0, acc1);
+    // the second block of 128 output features may start past d_model: point it at the last row
+    const int n1 = n0 + BNH < d_model ? n0 + BNH : d_model - 1;
+    mainloop(H + (size_t)t0 * ldh, ldh, T - t0, Wd + (size_t)n0 * d_inter, Wd + (size_t)n1 * d_inter,
+             d_inter, d_model - n0, d_model - n1, KRuns{bt}, kt_begin, kt_end, lds, acc0, acc1);
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave >> 1, wn = wave & 1;

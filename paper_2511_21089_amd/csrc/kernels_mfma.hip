@@ -22,13 +22,16 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 constexpr int BM = 256;          // tokens per tile
 constexpr int BNH = 128;         // rows of each of the two B blocks
-constexpr int BK = 64;           // K elements per stage: one tile row is 128 bytes = 8 chunks of 16
-constexpr int THREADS = 256;
-constexpr int A_BYTES = BM * BK * 2;                 // 32768
-constexpr int B_BYTES = BNH * BK * 2;                // 16384
-constexpr int STAGE_BYTES = A_BYTES + 2 * B_BYTES;   // 65536
-constexpr int A_LOADS = A_BYTES / 1024 / 4;          // 1 KiB wave-loads per wave: 8
-constexpr int B_LOADS = B_BYTES / 1024 / 4;          // 4 per block
+constexpr int BK = 32;           // K elements per stage: one tile row is 64 bytes = 4 chunks of 16
+constexpr int NST = 4;           // LDS stages: tiles i+1 .. i+3 are in flight while tile i is used
+constexpr int A_BYTES = BM * BK * 2;                 // 16384
+constexpr int B_BYTES = BNH * BK * 2;                // 8192
+constexpr int STAGE_BYTES = A_BYTES + 2 * B_BYTES;   // 32768
+constexpr int LDS_BYTES = NST * STAGE_BYTES;         // 131072
+#ifndef MLPMOE_MFMA_WM
+#define MLPMOE_MFMA_WM 4
+#endif
+constexpr int MFMA_WM = MLPMOE_MFMA_WM;              // waves along M: 2 (4 waves) or 4 (8 waves)
 
 // 16 zero bytes: K chunks that fall past the end of a range are fetched from here.
 __device__ const uint32_t g_zero_chunk[4] = {0, 0, 0, 0};
@@ -40,6 +43,17 @@ typedef __attribute__((address_space(3))) void *lptr_t;
 __device__ __forceinline__ void dma16(const void *src, void *lds_dst)
 {
     __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)lds_dst, 16, 0, 0);
+}
+
+// Workgroup barrier that waits until at most N of this wave's direct-to-LDS loads (they return
+// in issue order) and none of its LDS reads are outstanding.  Written by hand because the
+// compiler's own barrier waits for every load, which would drain the multi-stage pipeline.
+template <int N>
+__device__ __forceinline__ void pipeline_barrier()
+{
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
+    __builtin_amdgcn_sched_barrier(0);
 }
 
 // Position in the flattened list of K tiles (ranges laid end to end).
@@ -75,32 +89,41 @@ __device__ __forceinline__ KCursor k_seek(const KR &kr, int tile)
         }
         tile -= n;
     }
-    c.run = kr.n_runs();
+    c.run = kr.n_runs() - 1;
+    c.k = kr.start(c.run);
     return c;
 }
 
-// LDS tile layout.  A stage holds A (256 rows), B0 (128 rows), B1 (128 rows), each row 128 bytes
-// = 8 chunks of 8 bf16.  Chunk c of row r is stored at chunk slot c ^ swz(r),
-// swz(r) = (r & 7) ^ ((r >> 3) & 1), so that the 16-byte reads of 32 consecutive rows at one
-// logical chunk fall on distinct banks.  Direct-to-LDS loads write 1 KiB = 8 whole rows per wave
+// LDS tile layout.  A stage holds A (256 rows), B0 (128 rows), B1 (128 rows), each row 64 bytes
+// = 4 chunks of 8 bf16.  Chunk c of row r is stored at chunk slot c ^ swz(r),
+// swz(r) = ((r >> 1) & 3) ^ ((r >> 3) & 1), so that the 16-byte reads of consecutive rows at one
+// logical chunk fall on distinct banks.  Direct-to-LDS loads write 1 KiB = 16 whole rows per wave
 // instruction, so the swizzle is applied on the global side: the lane that fills slot p of row r
 // fetches logical chunk p ^ swz(r).
 //
-// Main loop.  A_tile / B0_tile / B1_tile point at the first row of the tile (wave uniform);
+// Main loop, WM x 2 waves (WM = 2: 4 waves of 128 x (64+64) outputs; WM = 4: 8 waves of
+// 64 x (64+64)).  A_tile / B0_tile / B1_tile point at the first row of the tile (wave uniform);
 // a_valid / b0_valid / b1_valid are the rows that exist from there on (>= 1).  Rows past that
 // are clamped to the last valid row: their results are never stored and MFMA rows / columns do
 // not mix.  K chunks past the end of a range are read from a zero chunk, in A and in B.
-// Pipeline: two LDS stages; the loads of tile i+1 are issued at the top of iteration i and
-// waited for at the barrier that sits before the last K step, so that the first fragments of
-// tile i+1 are read while the last MFMAs of tile i run.  Fragments are double buffered in
-// registers one K step ahead.
-template <typename KR>
+// Pipeline: four LDS stages.  Iteration i computes tile i (two K steps of 16) while the direct
+// loads of tiles i+1, i+2 are in flight and those of tile i+3 are issued; the barrier between the
+// two K steps waits for tile i+1 only, and the first fragments of tile i+1 are read during the
+// second K step.  Fragments are double buffered in registers one K step ahead.
+template <int WM, typename KR>
 __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, int lda, int a_valid,
                                          const uint16_t *__restrict__ B0_tile,
                                          const uint16_t *__restrict__ B1_tile, int ldb, int b0_valid,
                                          int b1_valid, const KR &kr, int kt_begin, int kt_end, char *lds,
-                                         f32x16 (&acc0)[4][2], f32x16 (&acc1)[4][2])
+                                         f32x16 (&acc0)[8 / WM][2], f32x16 (&acc1)[8 / WM][2])
 {
+    constexpr int MI = 8 / WM;                    // 32-row MFMA tiles per wave along M
+    constexpr int NWAVES = WM * 2;
+    constexpr int A_LOADS = A_BYTES / 1024 / NWAVES;   // 1 KiB wave-loads per wave per tile
+    constexpr int B_LOADS = B_BYTES / 1024 / NWAVES;   // per B block
+    constexpr int N_LOADS = A_LOADS + 2 * B_LOADS;     // 8 (4 waves) or 4 (8 waves)
+    constexpr int N_SLOTS = MI * 2;               // slots of 2 MFMAs per K step
+    constexpr int N_PIECES = 4 + MI;              // fragment pieces per K step
     const int nk = kt_end - kt_begin;
     if (nk <= 0) return;
     const int tid = threadIdx.x;
@@ -109,22 +132,22 @@ __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, in
     const int wm = wave >> 1, wn = wave & 1;
 
     // ---- global side: per-lane byte offsets of this wave's loads, relative to the tile pointers
-    const int lr = lane >> 3;                     // row inside the 8-row slab of one wave-load
-    const int cs[2] = {(lane & 7) ^ lr, (lane & 7) ^ lr ^ 1};   // logical chunk for even / odd slabs
+    const int lr = lane >> 2;                     // row inside the 16-row slab of one wave-load
+    const int cl = (lane & 3) ^ ((lr >> 1) & 3) ^ ((lr >> 3) & 1);   // logical chunk this lane fetches
     unsigned a_off[A_LOADS], b0_off[B_LOADS], b1_off[B_LOADS];
 #pragma unroll
     for (int i = 0; i < A_LOADS; ++i) {
-        int r = (wave * A_LOADS + i) * 8 + lr;
+        int r = (wave * A_LOADS + i) * 16 + lr;
         r = r < a_valid ? r : a_valid - 1;
-        a_off[i] = (unsigned)r * (unsigned)lda * 2u + (unsigned)cs[i & 1] * 16u;
+        a_off[i] = (unsigned)r * (unsigned)lda * 2u + (unsigned)cl * 16u;
     }
 #pragma unroll
     for (int i = 0; i < B_LOADS; ++i) {
-        const int r = (wave * B_LOADS + i) * 8 + lr;
+        const int r = (wave * B_LOADS + i) * 16 + lr;
         const int r0 = r < b0_valid ? r : b0_valid - 1;
         const int r1 = r < b1_valid ? r : b1_valid - 1;
-        b0_off[i] = (unsigned)r0 * (unsigned)ldb * 2u + (unsigned)cs[i & 1] * 16u;
-        b1_off[i] = (unsigned)r1 * (unsigned)ldb * 2u + (unsigned)cs[i & 1] * 16u;
+        b0_off[i] = (unsigned)r0 * (unsigned)ldb * 2u + (unsigned)cl * 16u;
+        b1_off[i] = (unsigned)r1 * (unsigned)ldb * 2u + (unsigned)cl * 16u;
     }
     const char *a_base = reinterpret_cast<const char *>(A_tile);
     const char *b0_base = reinterpret_cast<const char *>(B0_tile);
@@ -132,18 +155,26 @@ __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, in
     char *a_dst = lds + wave * (A_LOADS * 1024);
     char *b0_dst = lds + A_BYTES + wave * (B_LOADS * 1024);
     char *b1_dst = b0_dst + B_BYTES;
-
-    // Direct load number n (0..15) of the next tile: 0-7 A slabs, 8-11 B0, 12-15 B1.  Branch free
-    // on purpose, so that the loads sit in the same basic block as the MFMAs; a lane whose chunk
-    // lies past the end of the range (or with no tile left: kend very negative) reads the zero chunk.
     const char *zero = reinterpret_cast<const char *>(g_zero_chunk);
-    auto dma_n = [&](int n, int k, int kend, int stage) {
+
+    // Direct load number n of a tile: A slabs first, then B0, then B1.  A lane whose chunk lies
+    // past the end of the K range (last tile of a range), or any lane when no tile is left
+    // (kend very negative), reads the zero chunk instead.  Branch free, so that the loads sit in
+    // the same basic block as the MFMAs, and the count of loads per tile is always N_LOADS.
+    auto dma_n = [&](int n, const char *ua, const char *ub0, const char *ub1, bool ok, int stage) {
         const int so = stage * STAGE_BYTES;
-        const size_t kb = (size_t)k * 2;
-        const bool ok = k + cs[n & 1] * 8 < kend;
-        if (n < 8) dma16(ok ? a_base + kb + a_off[n] : zero, a_dst + so + n * 1024);
-        else if (n < 12) dma16(ok ? b0_base + kb + b0_off[n - 8] : zero, b0_dst + so + (n - 8) * 1024);
-        else dma16(ok ? b1_base + kb + b1_off[n - 12] : zero, b1_dst + so + (n - 12) * 1024);
+        if (n < A_LOADS) {
+            const char *src = ua + a_off[n];
+            dma16(ok ? src : zero, a_dst + so + n * 1024);
+        } else if (n < A_LOADS + B_LOADS) {
+            const int m = n - A_LOADS;
+            const char *src = ub0 + b0_off[m];
+            dma16(ok ? src : zero, b0_dst + so + m * 1024);
+        } else {
+            const int m = n - A_LOADS - B_LOADS;
+            const char *src = ub1 + b1_off[m];
+            dma16(ok ? src : zero, b1_dst + so + m * 1024);
+        }
     };
     auto advance = [&](KCursor &c) {      // stays on the last range once the list is exhausted
         c.k += BK;
@@ -153,74 +184,88 @@ __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, in
         }
     };
 
-    // ---- LDS side: per-lane read offsets (bytes) for the 4 K steps of a stage
+    // ---- LDS side: per-lane read offsets (bytes) for the 2 K steps of a stage
     const int lrow = lane & 31;
-    const int swz = (lane & 7) ^ ((lane >> 3) & 1);          // tile rows start at multiples of 32
-    int a_rd[BK / 16], b_rd[BK / 16];
+    const int swz = ((lane >> 1) & 3) ^ ((lane >> 3) & 1);   // tile rows start at multiples of 32
+    int a_rd[2], b_rd[2];
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
+    for (int ks = 0; ks < 2; ++ks) {
         const int slot = (ks * 2 + (lane >> 5)) ^ swz;
-        a_rd[ks] = (wm * 128 + lrow) * 128 + slot * 16;
-        b_rd[ks] = A_BYTES + (wn * 64 + lrow) * 128 + slot * 16;
+        a_rd[ks] = (wm * (MI * 32) + lrow) * 64 + slot * 16;
+        b_rd[ks] = A_BYTES + (wn * 64 + lrow) * 64 + slot * 16;
     }
     // Fragment pieces of one K step in the order they are read: the four B pieces first
-    // (b0[0], b1[0], b0[1], b1[1]), then a[0..3].  MFMA m uses a[m >> 2] and B piece m & 3, so the
-    // piece that is read last (a[3]) is needed only by the last four MFMAs of the following step.
+    // (b0[0], b1[0], b0[1], b1[1]), then a[0..MI).  MFMA m uses a[m >> 2] and B piece m & 3, so the
+    // piece that is read last is needed only by the last four MFMAs of the following step.
     struct Frags {
-        bf16x8 v[8];
+        bf16x8 v[N_PIECES];
     };
     auto read_piece = [&](Frags &f, int g, int stage, int ks) {
         const char *s = lds + stage * STAGE_BYTES;
-        if (g < 4) f.v[g] = *reinterpret_cast<const bf16x8 *>(s + b_rd[ks] + (g & 1) * B_BYTES + (g >> 1) * 4096);
-        else f.v[g] = *reinterpret_cast<const bf16x8 *>(s + a_rd[ks] + (g - 4) * 4096);
+        if (g < 4) f.v[g] = *reinterpret_cast<const bf16x8 *>(s + b_rd[ks] + (g & 1) * B_BYTES + (g >> 1) * 2048);
+        else f.v[g] = *reinterpret_cast<const bf16x8 *>(s + a_rd[ks] + (g - 4) * 2048);
     };
     auto mfma_n = [&](const Frags &f, int m) {
         const int i = m >> 2, j = (m >> 1) & 1;
         if (m & 1) acc1[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.v[4 + i], f.v[m & 3], acc1[i][j], 0, 0, 0);
         else acc0[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.v[4 + i], f.v[m & 3], acc0[i][j], 0, 0, 0);
     };
-    // One K step, written in the instruction order wanted: 8 slots of {2 MFMAs, then LDS reads of
-    // the next step's fragments, then one direct load of the next tile (optional)}; nothing may be
+    // One K step, written in the instruction order wanted: slots of {2 MFMAs, then LDS reads of
+    // the next step's fragments, then direct loads (first step of a tile only)}; nothing may be
     // moved across a slot boundary.  The compiler waits for ALL outstanding LDS reads before the
     // first MFMA of a step (direct-to-LDS loads in flight make it give up exact counting), so the
-    // eight reads are packed into slots 0-5 and the last two slots leave them time to land.
-    auto k_step = [&](const Frags &cur_f, Frags &nxt_f, int rd_stage, int rd_ks, int dma_first, int k,
-                      int kend, int dma_stage) {
+    // reads are packed into the early slots and the last slots leave them time to land.
+    auto k_step = [&](const Frags &cur_f, Frags &nxt_f, int rd_stage, int rd_ks, bool with_dma,
+                      const char *ua, const char *ub0, const char *ub1, bool ok, int dma_stage) {
 #pragma unroll
-        for (int g = 0; g < 8; ++g) {
+        for (int g = 0; g < N_SLOTS; ++g) {
             mfma_n(cur_f, 2 * g);
             mfma_n(cur_f, 2 * g + 1);
             __builtin_amdgcn_sched_barrier(0);
-            if (g < 2) {
-                read_piece(nxt_f, 2 * g, rd_stage, rd_ks);
-                read_piece(nxt_f, 2 * g + 1, rd_stage, rd_ks);
-            } else if (g < 6) {
-                read_piece(nxt_f, g + 2, rd_stage, rd_ks);
+            if (MI == 4) {                 // 8 pieces over slots 0-5: 2,2,1,1,1,1
+                if (g < 2) {
+                    read_piece(nxt_f, 2 * g, rd_stage, rd_ks);
+                    read_piece(nxt_f, 2 * g + 1, rd_stage, rd_ks);
+                } else if (g < 6) {
+                    read_piece(nxt_f, g + 2, rd_stage, rd_ks);
+                }
+            } else {                       // 6 pieces over slots 0-2: 2,2,2
+                if (g < 3) {
+                    read_piece(nxt_f, 2 * g, rd_stage, rd_ks);
+                    read_piece(nxt_f, 2 * g + 1, rd_stage, rd_ks);
+                }
             }
-            if (dma_first >= 0) dma_n(dma_first + g, k, kend, dma_stage);
+            if (with_dma) dma_n(g, ua, ub0, ub1, ok, dma_stage);   // N_LOADS == N_SLOTS
             __builtin_amdgcn_sched_barrier(0);
         }
     };
+    static_assert(N_LOADS == N_SLOTS, "one direct load per slot");
 
-    KCursor cur = k_seek(kr, kt_begin);
+    // prologue: tiles 0 .. NST-2 in flight, tile 0 landed
+    KCursor cur = k_seek(kr, kt_begin);           // cursor of the tile being ISSUED
 #pragma unroll
-    for (int n = 0; n < 16; ++n) dma_n(n, cur.k, kr.end(cur.run), 0);
-    __syncthreads();
+    for (int p = 0; p < NST - 1; ++p) {
+        const size_t kb = (size_t)cur.k * 2;
+        const bool ok = (p < nk) && (cur.k + cl * 8 < kr.end(cur.run));
+#pragma unroll
+        for (int n = 0; n < N_LOADS; ++n) dma_n(n, a_base + kb, b0_base + kb, b1_base + kb, ok, p);
+        advance(cur);
+    }
+    pipeline_barrier<(NST - 2) * N_LOADS>();
     Frags f0, f1;
 #pragma unroll
-    for (int g = 0; g < 8; ++g) read_piece(f0, g, 0, 0);
+    for (int g = 0; g < N_PIECES; ++g) read_piece(f0, g, 0, 0);
 
     for (int it = 0; it < nk; ++it) {
-        const int st = it & 1;
+        const int st = it & (NST - 1);
+        const size_t kb = (size_t)cur.k * 2;
+        const bool ok = (it + NST - 1 < nk) && (cur.k + cl * 8 < kr.end(cur.run));
+        k_step(f0, f1, st, 1, true, a_base + kb, b0_base + kb, b1_base + kb, ok, (it + NST - 1) & (NST - 1));
         advance(cur);
-        const int kend = it + 1 < nk ? kr.end(cur.run) : -(1 << 30);
-        k_step(f0, f1, st, 1, 0, cur.k, kend, st ^ 1);
-        k_step(f1, f0, st, 2, 8, cur.k, kend, st ^ 1);
-        k_step(f0, f1, st, 3, -1, 0, 0, 0);
-        __syncthreads();                          // tile it+1 has landed; stage st is free again
-        k_step(f1, f0, st ^ 1, 0, -1, 0, 0, 0);   // (after the last tile this reads zeros, unused)
+        pipeline_barrier<(NST - 2) * N_LOADS>();  // tile it+1 has landed; stage of tile it is free again
+        k_step(f1, f0, (it + 1) & (NST - 1), 0, false, nullptr, nullptr, nullptr, false, 0);
     }
-    __syncthreads();                              // LDS may be reused by the caller
+    pipeline_barrier<0>();                        // LDS may be reused by the caller
 }
 
 __device__ __forceinline__ int branch_of(const BranchTable &bt, int j)
@@ -244,12 +289,13 @@ __device__ __forceinline__ uint16_t to_bf16(float v)
 }
 
 // grid.x = tilesM * (sum over runs of N tiles); tile id -> (m tile fastest, n tile).
-__global__ void __launch_bounds__(THREADS)
+template <int WM>
+__global__ void __launch_bounds__(WM * 128)
 gate_up_mfma(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
              const uint16_t *__restrict__ Wu, uint16_t *__restrict__ H, int T, int d_model, int d_inter,
              int ldh, int tiles_m, BranchTable bt)
 {
-    __shared__ __attribute__((aligned(1024))) char lds[2 * STAGE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char lds[LDS_BYTES];
     const int tm = blockIdx.x % tiles_m;
     int tn = blockIdx.x / tiles_m;
     int n0 = 0, n_end = 0;
@@ -265,9 +311,10 @@ gate_up_mfma(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
     if (n_end == 0) return;
     const int t0 = tm * BM;
 
-    f32x16 accg[4][2], accu[4][2];
+    constexpr int MI = 8 / WM;
+    f32x16 accg[MI][2], accu[MI][2];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -277,7 +324,7 @@ gate_up_mfma(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
             }
 
     const int nk = (d_model + BK - 1) / BK;
-    mainloop(X + (size_t)t0 * d_model, d_model, T - t0, Wg + (size_t)n0 * d_model,
+    mainloop<WM>(X + (size_t)t0 * d_model, d_model, T - t0, Wg + (size_t)n0 * d_model,
              Wu + (size_t)n0 * d_model, d_model, n_end - n0, n_end - n0, KSingle{d_model}, 0, nk, lds,
              accg, accu);
 
@@ -289,10 +336,10 @@ gate_up_mfma(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
         if (n >= n_end) continue;
         const float al = bt.alpha[branch_of(bt, n)];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < MI; ++i) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int t = t0 + wm * 128 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                const int t = t0 + wm * (MI * 32) + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
                 if (t < T) H[(size_t)t * ldh + n] = to_bf16(al * silu_mul(accg[i][j][v], accu[i][j][v]));
             }
         }
@@ -300,12 +347,13 @@ gate_up_mfma(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
 }
 
 // grid.x = tilesM * tilesN * splits; dst = out (splits == 1) or partial[split][T][d_model].
-__global__ void __launch_bounds__(THREADS)
+template <int WM>
+__global__ void __launch_bounds__(WM * 128)
 down_mfma(const uint16_t *__restrict__ H, const uint16_t *__restrict__ Wd, float *__restrict__ dst, int T,
           int d_model, int d_inter, int ldh, int tiles_m, int tiles_n, int splits, int kt_total,
           BranchTable bt)
 {
-    __shared__ __attribute__((aligned(1024))) char lds[2 * STAGE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char lds[LDS_BYTES];
     int id = blockIdx.x;
     const int tm = id % tiles_m;
     id /= tiles_m;
@@ -315,9 +363,10 @@ down_mfma(const uint16_t *__restrict__ H, const uint16_t *__restrict__ Wd, float
     const int kt_begin = (int)((long long)kt_total * z / splits);
     const int kt_end = (int)((long long)kt_total * (z + 1) / splits);
 
-    f32x16 acc0[4][2], acc1[4][2];
+    constexpr int MI = 8 / WM;
+    f32x16 acc0[MI][2], acc1[MI][2];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -328,7 +377,7 @@ down_mfma(const uint16_t *__restrict__ H, const uint16_t *__restrict__ Wd, float
 
     // the second block of 128 output features may start past d_model: point it at the last row
     const int n1 = n0 + BNH < d_model ? n0 + BNH : d_model - 1;
-    mainloop(H + (size_t)t0 * ldh, ldh, T - t0, Wd + (size_t)n0 * d_inter, Wd + (size_t)n1 * d_inter,
+    mainloop<WM>(H + (size_t)t0 * ldh, ldh, T - t0, Wd + (size_t)n0 * d_inter, Wd + (size_t)n1 * d_inter,
              d_inter, d_model - n0, d_model - n1, KRuns{bt}, kt_begin, kt_end, lds, acc0, acc1);
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -341,10 +390,10 @@ down_mfma(const uint16_t *__restrict__ H, const uint16_t *__restrict__ Wd, float
             const int n = n0 + half * BNH + wn * 64 + j * 32 + (lane & 31);
             if (n >= d_model) continue;
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < MI; ++i)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const int t = t0 + wm * 128 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                    const int t = t0 + wm * (MI * 32) + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
                     if (t < T) o[(size_t)t * d_model + n] = half ? acc1[i][j][v] : acc0[i][j][v];
                 }
         }
@@ -404,7 +453,7 @@ hipError_t launch_mfma_bf16(const FwdArgs &a, const BranchTable &bt)
 
     {
     ProfileScope ps(MLPMOE_KERNEL_GATE_UP_MFMA, a.stream);
-    gate_up_mfma<<<(unsigned)grid1, THREADS, 0, a.stream>>>(
+    gate_up_mfma<MFMA_WM><<<(unsigned)grid1, MFMA_WM * 128, 0, a.stream>>>(
         static_cast<const uint16_t *>(a.x), static_cast<const uint16_t *>(a.Wg),
         static_cast<const uint16_t *>(a.Wu), static_cast<uint16_t *>(a.H), a.T, a.d_model, a.d_inter,
         a.ldh, tiles_m, bt);
@@ -412,7 +461,7 @@ hipError_t launch_mfma_bf16(const FwdArgs &a, const BranchTable &bt)
     float *dst = splits > 1 ? a.partial : a.out;
     {
     ProfileScope ps(MLPMOE_KERNEL_DOWN_MFMA, a.stream);
-    down_mfma<<<(unsigned)grid2, THREADS, 0, a.stream>>>(
+    down_mfma<MFMA_WM><<<(unsigned)grid2, MFMA_WM * 128, 0, a.stream>>>(
         static_cast<const uint16_t *>(a.H), static_cast<const uint16_t *>(a.Wd), dst, a.T, a.d_model,
         a.d_inter, a.ldh, tiles_m, tiles_n2, splits, kt_total, bt);
     }

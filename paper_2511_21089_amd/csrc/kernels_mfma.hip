@@ -288,16 +288,38 @@ __device__ __forceinline__ uint16_t to_bf16(float v)
     return __builtin_bit_cast(uint16_t, b);
 }
 
-// grid.x = tilesM * (sum over runs of N tiles); tile id -> (m tile fastest, n tile).
+// Workgroup id -> output tile.  The hardware deals consecutive workgroup ids round-robin to the
+// 8 XCDs, each with its own L2.  Every XCD therefore takes one contiguous eighth of a "grouped"
+// tile order (groups of 8 M tiles, M fastest inside a group), so that the 32 workgroups resident
+// on an XCD form an 8 x 4 block of tiles and share their A and B tiles through that L2.
+// The grid holds 8 * ceil(tiles / 8) ids; ids past the end get no tile.
+constexpr int XCDS = 8;
+constexpr int GROUP_M = 8;
+__host__ __device__ inline int ids_per_xcd(long long tiles) { return (int)((tiles + XCDS - 1) / XCDS); }
+__device__ __forceinline__ bool tile_of(int id, int tiles_m, int tiles_n, int &tm, int &tn)
+{
+    const int total = tiles_m * tiles_n;
+    const int logical = (id % XCDS) * ids_per_xcd(total) + id / XCDS;
+    if (logical >= total) return false;
+    const int group_sz = GROUP_M * tiles_n;
+    const int g = logical / group_sz, rem = logical % group_sz;
+    const int m0 = g * GROUP_M;
+    const int gsz = tiles_m - m0 < GROUP_M ? tiles_m - m0 : GROUP_M;
+    tm = m0 + rem % gsz;
+    tn = rem / gsz;
+    return true;
+}
+
+// grid.x = 8 * ids_per_xcd(tilesM * sum over runs of N tiles).
 template <int WM>
 __global__ void __launch_bounds__(WM * 128)
 gate_up_mfma(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
              const uint16_t *__restrict__ Wu, uint16_t *__restrict__ H, int T, int d_model, int d_inter,
-             int ldh, int tiles_m, BranchTable bt)
+             int ldh, int tiles_m, int tiles_n, BranchTable bt)
 {
     __shared__ __attribute__((aligned(1024))) char lds[LDS_BYTES];
-    const int tm = blockIdx.x % tiles_m;
-    int tn = blockIdx.x / tiles_m;
+    int tm, tn;
+    if (!tile_of(blockIdx.x, tiles_m, tiles_n, tm, tn)) return;
     int n0 = 0, n_end = 0;
     for (int r = 0; r < bt.n_runs; ++r) {
         const int n = (bt.run_end[r] - bt.run_start[r] + BNH - 1) / BNH;
@@ -346,7 +368,7 @@ gate_up_mfma(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
     }
 }
 
-// grid.x = tilesM * tilesN * splits; dst = out (splits == 1) or partial[split][T][d_model].
+// grid.x = splits * 8 * ids_per_xcd(tilesM * tilesN); dst = out (splits == 1) or partial[split][T][d_model].
 template <int WM>
 __global__ void __launch_bounds__(WM * 128)
 down_mfma(const uint16_t *__restrict__ H, const uint16_t *__restrict__ Wd, float *__restrict__ dst, int T,
@@ -354,11 +376,10 @@ down_mfma(const uint16_t *__restrict__ H, const uint16_t *__restrict__ Wd, float
           BranchTable bt)
 {
     __shared__ __attribute__((aligned(1024))) char lds[LDS_BYTES];
-    int id = blockIdx.x;
-    const int tm = id % tiles_m;
-    id /= tiles_m;
-    const int tn = id % tiles_n;
-    const int z = id / tiles_n;
+    const int per_split = XCDS * ids_per_xcd((long long)tiles_m * tiles_n);
+    const int z = blockIdx.x / per_split;
+    int tm, tn;
+    if (!tile_of(blockIdx.x % per_split, tiles_m, tiles_n, tm, tn)) return;
     const int t0 = tm * BM, n0 = tn * (2 * BNH);
     const int kt_begin = (int)((long long)kt_total * z / splits);
     const int kt_end = (int)((long long)kt_total * (z + 1) / splits);
@@ -441,14 +462,14 @@ hipError_t launch_mfma_bf16(const FwdArgs &a, const BranchTable &bt)
     const int tiles_m = ceil_div(a.T, BM);
     long long tiles_n1 = 0;
     for (int r = 0; r < bt.n_runs; ++r) tiles_n1 += ceil_div(bt.run_end[r] - bt.run_start[r], BNH);
-    const long long grid1 = tiles_m * tiles_n1;
+    const long long grid1 = (long long)XCDS * ids_per_xcd(tiles_m * tiles_n1);
     const int tiles_n2 = ceil_div(a.d_model, 2 * BNH);
     // splits from the active width: never more than the workspace was sized for (d_inter >= d_eff)
     int splits = mfma_down_splits(a.T, a.d_model, bt.d_eff);
     const int kt_total = k_tiles(bt);
     if (splits > kt_total) splits = kt_total;
     if (splits > 1 && (size_t)splits * a.T * a.d_model * sizeof(float) > a.partial_bytes) splits = 1;
-    const long long grid2 = (long long)tiles_m * tiles_n2 * splits;
+    const long long grid2 = (long long)XCDS * ids_per_xcd((long long)tiles_m * tiles_n2) * splits;
     if (grid1 > 0x7fffffffLL || grid2 > 0x7fffffffLL) return hipErrorInvalidValue;
 
     {
@@ -456,7 +477,7 @@ hipError_t launch_mfma_bf16(const FwdArgs &a, const BranchTable &bt)
     gate_up_mfma<MFMA_WM><<<(unsigned)grid1, MFMA_WM * 128, 0, a.stream>>>(
         static_cast<const uint16_t *>(a.x), static_cast<const uint16_t *>(a.Wg),
         static_cast<const uint16_t *>(a.Wu), static_cast<uint16_t *>(a.H), a.T, a.d_model, a.d_inter,
-        a.ldh, tiles_m, bt);
+        a.ldh, tiles_m, (int)tiles_n1, bt);
     }
     float *dst = splits > 1 ? a.partial : a.out;
     {

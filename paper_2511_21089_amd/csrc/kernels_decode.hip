@@ -7,10 +7,14 @@
 // pieces of every row, and the waves' partial 16x16 results are summed through LDS in a
 // fixed order (deterministic).
 //
-//   decode_gate_up:  rows = neurons of W_gate and W_up, K = d_model,
-//                    epilogue h = bf16(alpha_b * SiLU(g) * u)            (Sec. 3.1 inner bracket)
-//   decode_down:     rows = output features of W_down, K = active runs of neurons,
+//   decode_gate_up:  a tile is 8 neurons: MFMA rows 0-7 are their W_gate rows, rows 8-15 their
+//                    W_up rows, K = d_model; epilogue h = bf16(alpha_b * SiLU(g) * u)
+//                                                                        (Sec. 3.1 inner bracket)
+//   decode_down:     a tile is 16 output features of W_down, K = active runs of neurons,
 //                    epilogue out[t,m] = sum                            (Sec. 3.1 outer sum)
+//
+// Eight-neuron tiles keep the tile count a multiple of the CU count for the usual widths
+// (14336 / 8 = 7 * 256) and never straddle a run boundary (boundaries are multiples of 8).
 #include "internal.h"
 
 namespace mlpmoe {
@@ -22,7 +26,15 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 constexpr int KB = 64;   // K elements per wave step: two MFMA steps, 32 contiguous bytes per lane
 
-__device__ __forceinline__ u32x4 ld16(const uint16_t *p) { return *reinterpret_cast<const u32x4 *>(p); }
+// 16 zero bytes: lanes with nothing to load (token >= T, K chunk past the end of a range) read here.
+__device__ const uint32_t g_zero16[4] = {0, 0, 0, 0};
+
+// 16-byte load through the global (not flat) path: every pointer handed in is device memory.
+__device__ __forceinline__ u32x4 ld16(const uint16_t *p)
+{
+    typedef const __attribute__((address_space(1))) u32x4 *gptr;
+    return *(gptr)(const void *)p;
+}
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 __device__ __forceinline__ float silu_mul(float g, float u)
@@ -48,123 +60,323 @@ __device__ __forceinline__ int branch_of(const BranchTable &bt, int j)
 // K values of group q = l >> 4.  A lane here loads 16 contiguous K values k0+16q .. k0+16q+15
 // and feeds the low 8 to one MFMA and the high 8 to the next; x is loaded with the same
 // mapping, so the permutation of K inside a block cancels out.
-template <int NW, bool kGateUp>
+//
+// Memory-level parallelism: every wave keeps the loads of U of its K blocks in flight (a ring of
+// U register sets: block i is consumed, then the load of block i+U is issued into its place).
+// All loads are branch free: a lane with nothing to load points at a zero chunk instead.
+template <int NW, int U, bool kGateUp>
 __global__ void __launch_bounds__(NW * 64)
 decode_kernel(const uint16_t *__restrict__ Xin, int ldx, int T,
               const uint16_t *__restrict__ W0, const uint16_t *__restrict__ W1, int ldw,
               int d_model, uint16_t *__restrict__ Hout, int ldh, float *__restrict__ out,
               BranchTable bt)
 {
-    __shared__ float red[NW][2][256];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    static_assert(NW >= 4, "the final reduction uses 256 threads");
+    __shared__ float red[NW][256];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int r16 = lane & 15, q = lane >> 4;
 
-    // tile -> first row and number of valid rows
-    int row0 = 0, row_end = 0;
+    // tile -> this lane's weight row
+    int row0 = 0;
+    const uint16_t *wrow;
     if (kGateUp) {
         int tile = blockIdx.x;
+        int found = 0;
         for (int r = 0; r < bt.n_runs; ++r) {
-            const int n = (bt.run_end[r] - bt.run_start[r] + 15) / 16;
+            const int n = (bt.run_end[r] - bt.run_start[r]) / 8;     // run lengths are multiples of 8
             if (tile < n) {
-                row0 = bt.run_start[r] + tile * 16;
-                row_end = bt.run_end[r];
+                row0 = bt.run_start[r] + tile * 8;
+                found = 1;
                 break;
             }
             tile -= n;
         }
-        if (row_end == 0) return;
+        if (!found) return;
+        wrow = (r16 < 8 ? W0 : W1) + (size_t)(row0 + (r16 & 7)) * ldw;
     } else {
         row0 = blockIdx.x * 16;
-        row_end = d_model;
+        int m = row0 + r16;
+        m = m < d_model ? m : d_model - 1;               // clamped rows are computed but never stored
+        wrow = W0 + (size_t)m * ldw;
     }
-    int wrow = row0 + r16;
-    wrow = wrow < row_end ? wrow : row_end - 1;          // clamped rows are computed but never stored
-    const uint16_t *w0 = W0 + (size_t)wrow * ldw + q * 16;
-    const uint16_t *w1 = kGateUp ? W1 + (size_t)wrow * ldw + q * 16 : nullptr;
+    wrow += q * 16;
     const bool tok = r16 < T;
     const uint16_t *xp = Xin + (size_t)(tok ? r16 : 0) * ldx + q * 16;
+    const uint16_t *zero = reinterpret_cast<const uint16_t *>(g_zero16);
 
-    f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
-    const u32x4 z = {0, 0, 0, 0};
-
+    // cursor over this wave's blocks: (range, block inside the range); ranges laid end to end
     const int n_ranges = kGateUp ? 1 : bt.n_runs;
-    int skip = wave;                                     // blocks to skip before this wave's next one
-    for (int r = 0; r < n_ranges; ++r) {
-        const int kbeg = kGateUp ? 0 : bt.run_start[r];
-        const int kend = kGateUp ? d_model : bt.run_end[r];
-        const int nblk = (kend - kbeg + KB - 1) / KB;
-        int blk = skip;
-#pragma unroll 4
-        for (; blk < nblk; blk += NW) {
-            const int k = kbeg + blk * KB;
-            const int kl = k + q * 16;
-            const bool ok0 = kl < kend, ok1 = kl + 8 < kend;
-            const u32x4 a00 = ok0 ? ld16(w0 + k) : z;
-            const u32x4 a01 = ok1 ? ld16(w0 + k + 8) : z;
-            const u32x4 x0 = (ok0 && tok) ? ld16(xp + k) : z;
-            const u32x4 x1 = (ok1 && tok) ? ld16(xp + k + 8) : z;
-            acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a00), as_bf16x8(x0), acc0, 0, 0, 0);
-            acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a01), as_bf16x8(x1), acc0, 0, 0, 0);
-            if (kGateUp) {
-                const u32x4 a10 = ok0 ? ld16(w1 + k) : z;
-                const u32x4 a11 = ok1 ? ld16(w1 + k + 8) : z;
-                acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a10), as_bf16x8(x0), acc1, 0, 0, 0);
-                acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a11), as_bf16x8(x1), acc1, 0, 0, 0);
-            }
+    auto rbeg = [&](int r) { return kGateUp ? 0 : bt.run_start[r]; };
+    auto rend = [&](int r) { return kGateUp ? d_model : bt.run_end[r]; };
+    int cr = 0, cb = wave;                               // load cursor
+    auto settle = [&]() {                                // move past ranges the block index overshoots
+        while (cr < n_ranges) {
+            const int nb = (rend(cr) - rbeg(cr) + KB - 1) / KB;
+            if (cb < nb) break;
+            cb -= nb;
+            ++cr;
         }
-        skip = blk - nblk;                               // carry the interleave across runs
+    };
+    settle();
+    int total = 0;                                       // blocks of this wave in all ranges
+    {
+        int sk = wave;
+        for (int r = 0; r < n_ranges; ++r) {
+            const int nb = (rend(r) - rbeg(r) + KB - 1) / KB;
+            const int mine = nb > sk ? (nb - sk + NW - 1) / NW : 0;
+            total += mine;
+            sk = sk + mine * NW - nb;
+        }
+    }
+
+    u32x4 wa[U][2], xa[U][2];
+    auto load_block = [&](int u) {                       // loads the block under the cursor, then advances
+        const bool live = cr < n_ranges;
+        const int k = live ? rbeg(cr) + cb * KB : 0;
+        const int kend = live ? rend(cr) : -1;
+        const int kl = k + q * 16;
+        const bool ok0 = kl < kend, ok1 = kl + 8 < kend;
+        wa[u][0] = ld16(ok0 ? wrow + k : zero);
+        wa[u][1] = ld16(ok1 ? wrow + k + 8 : zero);
+        xa[u][0] = ld16((ok0 && tok) ? xp + k : zero);
+        xa[u][1] = ld16((ok1 && tok) ? xp + k + 8 : zero);
+        cb += NW;
+        settle();
+    };
+
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int u = 0; u < U; ++u) load_block(u);
+    for (int j = 0; j < total; j += U) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(wa[u][0]), as_bf16x8(xa[u][0]), acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(wa[u][1]), as_bf16x8(xa[u][1]), acc, 0, 0, 0);
+            load_block(u);                               // past the last block this loads zeros
+        }
     }
 
     // cross-wave sum in wave order
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
-        red[wave][0][v * 64 + lane] = acc0[v];
-        if (kGateUp) red[wave][1][v * 64 + lane] = acc1[v];
-    }
+    for (int v = 0; v < 4; ++v) red[wave][v * 64 + lane] = acc[v];
     __syncthreads();
     if (threadIdx.x >= 256) return;
-    const int v = threadIdx.x >> 6;                      // accumulator register index 0..3
-    float s0 = 0.f, s1 = 0.f;
-#pragma unroll
-    for (int w = 0; w < NW; ++w) {
-        s0 += red[w][0][threadIdx.x];
-        if (kGateUp) s1 += red[w][1][threadIdx.x];
-    }
     // accumulator layout: register v of lane l is D[row 4*(l>>4)+v][col l&15]
-    const int row = row0 + 4 * q + v;
+    const int v = threadIdx.x >> 6;
+    const int row = 4 * q + v;
     const int t = r16;
-    if (t >= T || row >= row_end) return;
+    if (t >= T) return;
     if (kGateUp) {
-        const float al = bt.alpha[branch_of(bt, row)];
-        Hout[(size_t)t * ldh + row] = to_bf16(al * silu_mul(s0, s1));
+        if (row >= 8) return;                            // rows 8-15 hold the up projection of rows 0-7
+        float g = 0.f, up = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            g += red[w][threadIdx.x];
+            up += red[w][threadIdx.x + 32];              // row + 8: two lane groups further
+        }
+        const int n = row0 + row;
+        const float al = bt.alpha[branch_of(bt, n)];
+        Hout[(size_t)t * ldh + n] = to_bf16(al * silu_mul(g, up));
     } else {
-        out[(size_t)t * d_model + row] = s0;
+        float s0 = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) s0 += red[w][threadIdx.x];
+        const int m = row0 + row;
+        if (m < d_model) out[(size_t)t * d_model + m] = s0;
     }
 }
+
+// Persistent gate+up kernel for layers whose x fits in LDS (T * (d_model*2 + 16) bytes).
+// One workgroup per CU copies x into LDS once and then walks its tiles (tile t belongs to
+// workgroup t % grid, so every CU gets the same number).  The NW waves of the workgroup share each
+// tile with interleaved 64-element K blocks, which makes the workgroup read NW*128 contiguous
+// bytes of every weight row per step; every wave keeps a ring of U blocks in flight, and the ring
+// keeps rolling across tile boundaries, so the loads of the next tile are already under way
+// while the partial sums of the current one are reduced through LDS (one barrier per tile, the
+// reduction buffer is double buffered).  Each wave's block count per tile is padded to a
+// multiple of U with blocks that read a zero chunk, which keeps ring slots compile-time constants.
+// x rows are padded by 16 bytes so that the 16 token rows of a fragment fall on distinct banks.
+template <int NW, int U>
+__global__ void __launch_bounds__(NW * 64)
+decode_gate_up_persist(const uint16_t *__restrict__ X, int T, const uint16_t *__restrict__ Wg,
+                       const uint16_t *__restrict__ Wu, int d_model, uint16_t *__restrict__ Hout, int ldh,
+                       int tiles, BranchTable bt)
+{
+    static_assert(NW >= 4, "the reduction uses 256 threads");
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    float *red = reinterpret_cast<float *>(smem);                 // [2][NW][256]
+    char *xs = smem + 2 * NW * 256 * sizeof(float);
+    const int row_bytes = d_model * 2 + 16;
+    const int zero_off = T * row_bytes;                  // 16 zero bytes after the last row
+    {
+        const int chunks = T * (d_model / 8);            // 16-byte chunks of x
+        for (int i0 = 0; i0 < chunks; i0 += NW * 64 * 8) {
+            u32x4 v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {                // 8 loads in flight per thread
+                const int i = i0 + j * (NW * 64) + threadIdx.x;
+                v[j] = ld16(i < chunks ? X + (size_t)i * 8 : reinterpret_cast<const uint16_t *>(g_zero16));
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int i = i0 + j * (NW * 64) + threadIdx.x;
+                if (i < chunks) {
+                    const int t = i / (d_model / 8), c = i % (d_model / 8);
+                    *reinterpret_cast<u32x4 *>(xs + t * row_bytes + c * 16) = v[j];
+                }
+            }
+        }
+    }
+    if (threadIdx.x == 0) *reinterpret_cast<u32x4 *>(xs + zero_off) = u32x4{0, 0, 0, 0};
+    __syncthreads();
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int r16 = lane & 15, q = lane >> 4;
+    const bool tok = r16 < T;
+    const int x_lane = (tok ? r16 : 0) * row_bytes + q * 32;
+    const uint16_t *zero = reinterpret_cast<const uint16_t *>(g_zero16);
+    const int nblk = (d_model + KB - 1) / KB;
+    const int nb_pad = ((nblk + NW - 1) / NW + U - 1) / U * U;    // blocks per wave per tile, padded
+    const size_t lane_row_off = (size_t)(r16 & 7) * d_model + q * 16;
+    const uint16_t *wsel = r16 < 8 ? Wg : Wu;
+
+    auto tile_row0 = [&](int tile) {
+        int tt = tile;
+        for (int r = 0; r < bt.n_runs; ++r) {
+            const int n = (bt.run_end[r] - bt.run_start[r]) / 8;
+            if (tt < n) return bt.run_start[r] + tt * 8;
+            tt -= n;
+        }
+        return -1;
+    };
+
+    // load cursor: U blocks ahead of the block being consumed
+    int l_tile = blockIdx.x, l_j = 0;
+    const uint16_t *l_wrow = wsel + (size_t)tile_row0(l_tile) * d_model + lane_row_off;
+    u32x4 wa[U][2];
+    auto load_next = [&](int u) {
+        const int b = wave + NW * l_j;                   // K block inside the tile
+        const int kl = b * KB + q * 16;
+        const bool live = l_tile < tiles;
+        wa[u][0] = ld16((live && kl < d_model) ? l_wrow + b * KB : zero);
+        wa[u][1] = ld16((live && kl + 8 < d_model) ? l_wrow + b * KB + 8 : zero);
+        if (++l_j == nb_pad) {
+            l_j = 0;
+            l_tile += gridDim.x;
+            if (l_tile < tiles) l_wrow = wsel + (size_t)tile_row0(l_tile) * d_model + lane_row_off;
+        }
+    };
+#pragma unroll
+    for (int u = 0; u < U; ++u) load_next(u);
+
+    int it = 0;
+    for (int tile = blockIdx.x; tile < tiles; tile += gridDim.x, ++it) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        for (int j0 = 0; j0 < nb_pad; j0 += U) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int b = wave + NW * (j0 + u);
+                const int kl = b * KB + q * 16;
+                const int xo0 = (tok && kl < d_model) ? x_lane + b * (KB * 2) : zero_off;
+                const int xo1 = (tok && kl + 8 < d_model) ? x_lane + b * (KB * 2) + 16 : zero_off;
+                const bf16x8 x0 = *reinterpret_cast<const bf16x8 *>(xs + xo0);
+                const bf16x8 x1 = *reinterpret_cast<const bf16x8 *>(xs + xo1);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(wa[u][0]), x0, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(wa[u][1]), x1, acc, 0, 0, 0);
+                load_next(u);                            // refill the slot just consumed
+                __builtin_amdgcn_sched_barrier(0);       // keep the ring rolling: no batching of loads
+            }
+        }
+        // cross-wave sum in wave order; rows 0-7 hold g, rows 8-15 hold u of the same neurons
+        float *rb = red + (it & 1) * (NW * 256);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) rb[wave * 256 + v * 64 + lane] = acc[v];
+        __syncthreads();
+        if (threadIdx.x < 256) {
+            const int v = threadIdx.x >> 6;
+            const int row = 4 * q + v;                   // register v of lane l is D[row 4*(l>>4)+v][col l&15]
+            if (row < 8 && tok) {
+                float g = 0.f, up = 0.f;
+#pragma unroll
+                for (int w = 0; w < NW; ++w) {
+                    g += rb[w * 256 + threadIdx.x];
+                    up += rb[w * 256 + threadIdx.x + 32];
+                }
+                const int n = tile_row0(tile) + row;
+                const float al = bt.alpha[branch_of(bt, n)];
+                Hout[(size_t)r16 * ldh + n] = to_bf16(al * silu_mul(g, up));
+            }
+        }
+    }
+}
+
+#ifndef MLPMOE_DEC_NW1
+#define MLPMOE_DEC_NW1 4
+#endif
+#ifndef MLPMOE_DEC_U1
+#define MLPMOE_DEC_U1 8
+#endif
+#ifndef MLPMOE_DEC_NW2
+#define MLPMOE_DEC_NW2 8
+#endif
+#ifndef MLPMOE_DEC_U2
+#define MLPMOE_DEC_U2 8
+#endif
+
+#ifndef MLPMOE_DEC_SNW
+#define MLPMOE_DEC_SNW 8
+#endif
+#ifndef MLPMOE_DEC_SU
+#define MLPMOE_DEC_SU 8
+#endif
+constexpr size_t kStreamLdsMax = 160 * 1024;
 
 }  // namespace
 
 hipError_t launch_decode_bf16(const FwdArgs &a, const BranchTable &bt)
 {
     long long tiles1 = 0;
-    for (int r = 0; r < bt.n_runs; ++r) tiles1 += ceil_div(bt.run_end[r] - bt.run_start[r], 16);
+    for (int r = 0; r < bt.n_runs; ++r) tiles1 += (bt.run_end[r] - bt.run_start[r]) / 8;
     const int tiles2 = ceil_div(a.d_model, 16);
     if (tiles1 > 0x7fffffffLL) return hipErrorInvalidValue;
     const uint16_t *X = static_cast<const uint16_t *>(a.x);
     uint16_t *H = static_cast<uint16_t *>(a.H);
-    {
-    ProfileScope ps(MLPMOE_KERNEL_DECODE_GATE_UP, a.stream);
-    decode_kernel<4, true><<<(unsigned)tiles1, 256, 0, a.stream>>>(
-        X, a.d_model, a.T, static_cast<const uint16_t *>(a.Wg), static_cast<const uint16_t *>(a.Wu),
-        a.d_model, a.d_model, H, a.ldh, nullptr, bt);
+    const size_t xs_bytes = (size_t)a.T * (a.d_model * 2 + 16) + 16 + 2 * MLPMOE_DEC_SNW * 256 * sizeof(float);
+    if (xs_bytes <= kStreamLdsMax) {
+        static int n_cus = 0;
+        static bool attr_set = false;
+        if (!attr_set) {
+            int dev = 0;
+            hipDeviceProp_t prop;
+            if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
+                return hipErrorUnknown;
+            n_cus = prop.multiProcessorCount;
+            hipError_t e = hipFuncSetAttribute(
+                reinterpret_cast<const void *>(&decode_gate_up_persist<MLPMOE_DEC_SNW, MLPMOE_DEC_SU>),
+                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kStreamLdsMax);
+            if (e != hipSuccess) return e;
+            attr_set = true;
+        }
+        const int grid = tiles1 < n_cus ? (int)tiles1 : n_cus;
+        ProfileScope ps(MLPMOE_KERNEL_DECODE_GATE_UP, a.stream);
+        decode_gate_up_persist<MLPMOE_DEC_SNW, MLPMOE_DEC_SU><<<grid, MLPMOE_DEC_SNW * 64, xs_bytes, a.stream>>>(
+            X, a.T, static_cast<const uint16_t *>(a.Wg), static_cast<const uint16_t *>(a.Wu), a.d_model, H,
+            a.ldh, (int)tiles1, bt);
+    } else {
+        ProfileScope ps(MLPMOE_KERNEL_DECODE_GATE_UP, a.stream);
+        decode_kernel<MLPMOE_DEC_NW1, MLPMOE_DEC_U1, true><<<(unsigned)tiles1, MLPMOE_DEC_NW1 * 64, 0, a.stream>>>(
+            X, a.d_model, a.T, static_cast<const uint16_t *>(a.Wg), static_cast<const uint16_t *>(a.Wu),
+            a.d_model, a.d_model, H, a.ldh, nullptr, bt);
     }
     ProfileScope ps(MLPMOE_KERNEL_DECODE_DOWN, a.stream);
     if (tiles2 >= 192)
-        decode_kernel<8, false><<<tiles2, 512, 0, a.stream>>>(
+        decode_kernel<MLPMOE_DEC_NW2, MLPMOE_DEC_U2, false><<<tiles2, MLPMOE_DEC_NW2 * 64, 0, a.stream>>>(
             H, a.ldh, a.T, static_cast<const uint16_t *>(a.Wd), nullptr, a.d_inter, a.d_model, nullptr,
             a.ldh, a.out, bt);
     else
-        decode_kernel<16, false><<<tiles2, 1024, 0, a.stream>>>(
+        decode_kernel<16, 4, false><<<tiles2, 1024, 0, a.stream>>>(
             H, a.ldh, a.T, static_cast<const uint16_t *>(a.Wd), nullptr, a.d_inter, a.d_model, nullptr,
             a.ldh, a.out, bt);
     return hipGetLastError();

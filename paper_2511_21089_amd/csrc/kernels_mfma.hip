@@ -9,8 +9,8 @@
 //           so the sum over branches of Sec. 3.1 is one fp32 accumulation with no per-branch
 //           round trip.  Small outputs are split along K into deterministic partial sums.
 //
-// Both kernels share one main loop: A rows (tokens) against two blocks of 128 B rows,
-// 4 waves in a 2x2 arrangement, each wave owning 128 x (64+64) outputs = 16 MFMA tiles.
+// Both kernels share one main loop: 256 A rows (tokens) against two blocks of 128 B rows,
+// 8 waves in a 4x2 arrangement, each wave owning 64 x (64+64) outputs = 8 MFMA tiles.
 #include "internal.h"
 
 namespace mlpmoe {
@@ -22,12 +22,10 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 constexpr int BM = 256;          // tokens per tile
 constexpr int BNH = 128;         // rows of each of the two B blocks
-constexpr int BK = 32;           // K elements per stage: one tile row is 64 bytes = 4 chunks of 16
-constexpr int NST = 4;           // LDS stages: tiles i+1 .. i+3 are in flight while tile i is used
-constexpr int A_BYTES = BM * BK * 2;                 // 16384
-constexpr int B_BYTES = BNH * BK * 2;                // 8192
-constexpr int STAGE_BYTES = A_BYTES + 2 * B_BYTES;   // 32768
-constexpr int LDS_BYTES = NST * STAGE_BYTES;         // 131072
+constexpr int BK = 64;           // K elements per tile: one tile row is 128 bytes = one cache line
+constexpr int PART_BYTES = 256 * BK * 2;             // 32768: the A rows, or the 128 + 128 B rows, of one K tile
+constexpr int N_PARTS = 5;                           // ring of parts: A0 B0 A1 B1 A2 | B2 A3 ...
+constexpr int LDS_BYTES = N_PARTS * PART_BYTES;      // 163840: the whole LDS of a CU
 #ifndef MLPMOE_MFMA_WM
 #define MLPMOE_MFMA_WM 4
 #endif
@@ -94,22 +92,28 @@ __device__ __forceinline__ KCursor k_seek(const KR &kr, int tile)
     return c;
 }
 
-// LDS tile layout.  A stage holds A (256 rows), B0 (128 rows), B1 (128 rows), each row 64 bytes
-// = 4 chunks of 8 bf16.  Chunk c of row r is stored at chunk slot c ^ swz(r),
-// swz(r) = ((r >> 1) & 3) ^ ((r >> 3) & 1), so that the 16-byte reads of consecutive rows at one
-// logical chunk fall on distinct banks.  Direct-to-LDS loads write 1 KiB = 16 whole rows per wave
-// instruction, so the swizzle is applied on the global side: the lane that fills slot p of row r
-// fetches logical chunk p ^ swz(r).
+// LDS layout.  The LDS is a ring of five 32 KiB parts.  A part holds 256 rows of 128 bytes
+// (8 chunks of 8 bf16): either the A rows (tokens) of one K tile, or its B rows (128 rows of
+// the first B block, then 128 of the second).  Parts are filled in the order A0 B0 A1 B1 A2 B2 ...,
+// part number s going to ring slot s % 5, so while K tile i is being used the parts of tile i+1
+// and the A part of tile i+2 are landing.  Chunk c of row r is stored at chunk slot c ^ swz(r),
+// swz(r) = (r & 7) ^ ((r >> 3) & 1), so that the 16-byte reads of 32 consecutive rows at one
+// logical chunk fall on distinct banks.  A direct-to-LDS wave load writes 1 KiB = 8 whole rows,
+// and each row is one full 128-byte line of global memory (half lines cost the same L2 -> CU
+// transfer as whole ones); the swizzle is applied on the global side: the lane that fills slot p
+// of row r fetches logical chunk p ^ swz(r).
 //
 // Main loop, WM x 2 waves (WM = 2: 4 waves of 128 x (64+64) outputs; WM = 4: 8 waves of
 // 64 x (64+64)).  A_tile / B0_tile / B1_tile point at the first row of the tile (wave uniform);
 // a_valid / b0_valid / b1_valid are the rows that exist from there on (>= 1).  Rows past that
 // are clamped to the last valid row: their results are never stored and MFMA rows / columns do
 // not mix.  K chunks past the end of a range are read from a zero chunk, in A and in B.
-// Pipeline: four LDS stages.  Iteration i computes tile i (two K steps of 16) while the direct
-// loads of tiles i+1, i+2 are in flight and those of tile i+3 are issued; the barrier between the
-// two K steps waits for tile i+1 only, and the first fragments of tile i+1 are read during the
-// second K step.  Fragments are double buffered in registers one K step ahead.
+// Schedule of K tile i (four K steps of 16; fragments are double buffered one step ahead):
+//   step 0: MFMAs; read step 1's fragments; issue the A part of tile i+2 (one load per slot)
+//   step 1, 2: MFMAs; read the next step's fragments
+//   barrier: parts of tile i+1 have landed (only the newest A part may be in flight) and every
+//            wave has read its last fragments of tile i, whose two ring slots are free again
+//   step 3: MFMAs; read step 0's fragments of tile i+1; issue the B part of tile i+2
 template <int WM, typename KR>
 __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, int lda, int a_valid,
                                          const uint16_t *__restrict__ B0_tile,
@@ -119,11 +123,10 @@ __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, in
 {
     constexpr int MI = 8 / WM;                    // 32-row MFMA tiles per wave along M
     constexpr int NWAVES = WM * 2;
-    constexpr int A_LOADS = A_BYTES / 1024 / NWAVES;   // 1 KiB wave-loads per wave per tile
-    constexpr int B_LOADS = B_BYTES / 1024 / NWAVES;   // per B block
-    constexpr int N_LOADS = A_LOADS + 2 * B_LOADS;     // 8 (4 waves) or 4 (8 waves)
+    constexpr int PL = 32 / NWAVES;               // 1 KiB wave-loads per wave per part: 8 or 4
     constexpr int N_SLOTS = MI * 2;               // slots of 2 MFMAs per K step
     constexpr int N_PIECES = 4 + MI;              // fragment pieces per K step
+    static_assert(PL == N_SLOTS, "one direct load per slot");
     const int nk = kt_end - kt_begin;
     if (nk <= 0) return;
     const int tid = threadIdx.x;
@@ -132,67 +135,73 @@ __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, in
     const int wm = wave >> 1, wn = wave & 1;
 
     // ---- global side: per-lane byte offsets of this wave's loads, relative to the tile pointers
-    const int lr = lane >> 2;                     // row inside the 16-row slab of one wave-load
-    const int cl = (lane & 3) ^ ((lr >> 1) & 3) ^ ((lr >> 3) & 1);   // logical chunk this lane fetches
-    unsigned a_off[A_LOADS], b0_off[B_LOADS], b1_off[B_LOADS];
+    const int lr = lane >> 3;                     // row inside the 8-row slab of one wave-load
+    const int cl0 = (lane & 7) ^ lr;              // logical chunk fetched in even slabs; odd slabs: cl0 ^ 1
+    const bool second = wave >= NWAVES / 2;       // this wave fills the rows of the second B block
+    const int b_valid = second ? b1_valid : b0_valid;
+    unsigned a_off[PL], b_off[PL];
 #pragma unroll
-    for (int i = 0; i < A_LOADS; ++i) {
-        int r = (wave * A_LOADS + i) * 16 + lr;
-        r = r < a_valid ? r : a_valid - 1;
-        a_off[i] = (unsigned)r * (unsigned)lda * 2u + (unsigned)cl * 16u;
-    }
-#pragma unroll
-    for (int i = 0; i < B_LOADS; ++i) {
-        const int r = (wave * B_LOADS + i) * 16 + lr;
-        const int r0 = r < b0_valid ? r : b0_valid - 1;
-        const int r1 = r < b1_valid ? r : b1_valid - 1;
-        b0_off[i] = (unsigned)r0 * (unsigned)ldb * 2u + (unsigned)cl * 16u;
-        b1_off[i] = (unsigned)r1 * (unsigned)ldb * 2u + (unsigned)cl * 16u;
+    for (int n = 0; n < PL; ++n) {
+        const int slab = wave * PL + n;
+        const int cl = cl0 ^ (n & 1);             // PL is even, so slab parity is n parity
+        int ra = slab * 8 + lr;
+        ra = ra < a_valid ? ra : a_valid - 1;
+        int rb = (slab & 15) * 8 + lr;
+        rb = rb < b_valid ? rb : b_valid - 1;
+        a_off[n] = (unsigned)ra * (unsigned)lda * 2u + (unsigned)cl * 16u;
+        b_off[n] = (unsigned)rb * (unsigned)ldb * 2u + (unsigned)cl * 16u;
     }
     const char *a_base = reinterpret_cast<const char *>(A_tile);
-    const char *b0_base = reinterpret_cast<const char *>(B0_tile);
-    const char *b1_base = reinterpret_cast<const char *>(B1_tile);
-    char *a_dst = lds + wave * (A_LOADS * 1024);
-    char *b0_dst = lds + A_BYTES + wave * (B_LOADS * 1024);
-    char *b1_dst = b0_dst + B_BYTES;
+    const char *b_base = reinterpret_cast<const char *>(second ? B1_tile : B0_tile);
+    char *w_dst = lds + wave * (PL * 1024);       // this wave's slabs inside a part
     const char *zero = reinterpret_cast<const char *>(g_zero_chunk);
 
-    // Direct load number n of a tile: A slabs first, then B0, then B1.  A lane whose chunk lies
-    // past the end of the K range (last tile of a range), or any lane when no tile is left
-    // (kend very negative), reads the zero chunk instead.  Branch free, so that the loads sit in
-    // the same basic block as the MFMAs, and the count of loads per tile is always N_LOADS.
-    auto dma_n = [&](int n, const char *ua, const char *ub0, const char *ub1, bool ok, int stage) {
-        const int so = stage * STAGE_BYTES;
-        if (n < A_LOADS) {
-            const char *src = ua + a_off[n];
-            dma16(ok ? src : zero, a_dst + so + n * 1024);
-        } else if (n < A_LOADS + B_LOADS) {
-            const int m = n - A_LOADS;
-            const char *src = ub0 + b0_off[m];
-            dma16(ok ? src : zero, b0_dst + so + m * 1024);
-        } else {
-            const int m = n - A_LOADS - B_LOADS;
-            const char *src = ub1 + b1_off[m];
-            dma16(ok ? src : zero, b1_dst + so + m * 1024);
-        }
+    // Position of the next part to be issued, per matrix.  `left` counts the tiles not yet
+    // issued.  A lane whose chunk lies past the end of the K range, or any lane once no tile is
+    // left, reads the zero chunk instead.  Branch free, so that the loads sit in the same basic
+    // block as the MFMAs and every part is always PL loads.
+    struct Issue {
+        int run, k, kend, left, slot;
     };
-    auto advance = [&](KCursor &c) {      // stays on the last range once the list is exhausted
-        c.k += BK;
-        if (c.k >= kr.end(c.run) && c.run + 1 < kr.n_runs()) {
-            ++c.run;
-            c.k = kr.start(c.run);
+    auto advance = [&](Issue &q) {                // stays on the last range once the list is exhausted
+        q.k += BK;
+        if (q.k >= q.kend && q.run + 1 < kr.n_runs()) {
+            ++q.run;
+            q.k = kr.start(q.run);
+            q.kend = kr.end(q.run);
         }
+        --q.left;
+        q.slot += 2;
+        if (q.slot >= N_PARTS) q.slot -= N_PARTS;
+    };
+    // what the PL loads of one part have in common
+    struct Part {
+        const char *src;                          // tile pointer moved to the part's K offset
+        char *dst;                                // this wave's first slab in the part's ring slot
+        bool ok[2];                               // chunk inside the K range, for even / odd slabs
+    };
+    auto part_of = [&](const Issue &q, const char *base) {
+        Part pt;
+        const int kend = q.left > 0 ? q.kend : -(1 << 30);
+        pt.src = base + (size_t)q.k * 2;
+        pt.dst = w_dst + q.slot * PART_BYTES;
+        pt.ok[0] = q.k + cl0 * 8 < kend;
+        pt.ok[1] = q.k + (cl0 ^ 1) * 8 < kend;
+        return pt;
+    };
+    auto dma_part = [&](int n, const Part &pt, const unsigned (&off)[PL]) {
+        dma16(pt.ok[n & 1] ? pt.src + off[n] : zero, pt.dst + n * 1024);
     };
 
-    // ---- LDS side: per-lane read offsets (bytes) for the 2 K steps of a stage
+    // ---- LDS side: per-lane read offsets (bytes) for the 4 K steps of a tile
     const int lrow = lane & 31;
-    const int swz = ((lane >> 1) & 3) ^ ((lane >> 3) & 1);   // tile rows start at multiples of 32
-    int a_rd[2], b_rd[2];
+    const int swz = (lane & 7) ^ ((lane >> 3) & 1);      // fragment rows start at multiples of 32
+    int a_rd[4], b_rd[4];
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
+    for (int ks = 0; ks < 4; ++ks) {
         const int slot = (ks * 2 + (lane >> 5)) ^ swz;
-        a_rd[ks] = (wm * (MI * 32) + lrow) * 64 + slot * 16;
-        b_rd[ks] = A_BYTES + (wn * 64 + lrow) * 64 + slot * 16;
+        a_rd[ks] = (wm * (MI * 32) + lrow) * 128 + slot * 16;
+        b_rd[ks] = (wn * 64 + lrow) * 128 + slot * 16;
     }
     // Fragment pieces of one K step in the order they are read: the four B pieces first
     // (b0[0], b1[0], b0[1], b1[1]), then a[0..MI).  MFMA m uses a[m >> 2] and B piece m & 3, so the
@@ -200,10 +209,14 @@ __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, in
     struct Frags {
         bf16x8 v[N_PIECES];
     };
-    auto read_piece = [&](Frags &f, int g, int stage, int ks) {
-        const char *s = lds + stage * STAGE_BYTES;
-        if (g < 4) f.v[g] = *reinterpret_cast<const bf16x8 *>(s + b_rd[ks] + (g & 1) * B_BYTES + (g >> 1) * 2048);
-        else f.v[g] = *reinterpret_cast<const bf16x8 *>(s + a_rd[ks] + (g - 4) * 2048);
+    auto read_piece = [&](Frags &f, int g, int a_slot, int ks) {
+        // the B part of a tile sits in the ring slot after its A part
+        const int b_slot = a_slot + 1 < N_PARTS ? a_slot + 1 : 0;
+        if (g < 4)
+            f.v[g] = *reinterpret_cast<const bf16x8 *>(lds + b_slot * PART_BYTES + b_rd[ks] + (g & 1) * (128 * 128) +
+                                                       (g >> 1) * (32 * 128));
+        else
+            f.v[g] = *reinterpret_cast<const bf16x8 *>(lds + a_slot * PART_BYTES + a_rd[ks] + (g - 4) * (32 * 128));
     };
     auto mfma_n = [&](const Frags &f, int m) {
         const int i = m >> 2, j = (m >> 1) & 1;
@@ -211,12 +224,12 @@ __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, in
         else acc0[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.v[4 + i], f.v[m & 3], acc0[i][j], 0, 0, 0);
     };
     // One K step, written in the instruction order wanted: slots of {2 MFMAs, then LDS reads of
-    // the next step's fragments, then direct loads (first step of a tile only)}; nothing may be
+    // the next step's fragments, then one direct load (steps 0 and 3 only)}; nothing may be
     // moved across a slot boundary.  The compiler waits for ALL outstanding LDS reads before the
     // first MFMA of a step (direct-to-LDS loads in flight make it give up exact counting), so the
     // reads are packed into the early slots and the last slots leave them time to land.
-    auto k_step = [&](const Frags &cur_f, Frags &nxt_f, int rd_stage, int rd_ks, bool with_dma,
-                      const char *ua, const char *ub0, const char *ub1, bool ok, int dma_stage) {
+    // DMA: 0 none, 1 a load of the A part pt, 2 a load of the B part pt.
+    auto k_step = [&](const Frags &cur_f, Frags &nxt_f, int rd_slot, int rd_ks, int dma, const Part &pt) {
 #pragma unroll
         for (int g = 0; g < N_SLOTS; ++g) {
             mfma_n(cur_f, 2 * g);
@@ -224,46 +237,63 @@ __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, in
             __builtin_amdgcn_sched_barrier(0);
             if (MI == 4) {                 // 8 pieces over slots 0-5: 2,2,1,1,1,1
                 if (g < 2) {
-                    read_piece(nxt_f, 2 * g, rd_stage, rd_ks);
-                    read_piece(nxt_f, 2 * g + 1, rd_stage, rd_ks);
+                    read_piece(nxt_f, 2 * g, rd_slot, rd_ks);
+                    read_piece(nxt_f, 2 * g + 1, rd_slot, rd_ks);
                 } else if (g < 6) {
-                    read_piece(nxt_f, g + 2, rd_stage, rd_ks);
+                    read_piece(nxt_f, g + 2, rd_slot, rd_ks);
                 }
             } else {                       // 6 pieces over slots 0-2: 2,2,2
                 if (g < 3) {
-                    read_piece(nxt_f, 2 * g, rd_stage, rd_ks);
-                    read_piece(nxt_f, 2 * g + 1, rd_stage, rd_ks);
+                    read_piece(nxt_f, 2 * g, rd_slot, rd_ks);
+                    read_piece(nxt_f, 2 * g + 1, rd_slot, rd_ks);
                 }
             }
-            if (with_dma) dma_n(g, ua, ub0, ub1, ok, dma_stage);   // N_LOADS == N_SLOTS
+            if (dma == 1) dma_part(g, pt, a_off);
+            if (dma == 2) dma_part(g, pt, b_off);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
-    static_assert(N_LOADS == N_SLOTS, "one direct load per slot");
 
-    // prologue: tiles 0 .. NST-2 in flight, tile 0 landed
-    KCursor cur = k_seek(kr, kt_begin);           // cursor of the tile being ISSUED
-#pragma unroll
-    for (int p = 0; p < NST - 1; ++p) {
-        const size_t kb = (size_t)cur.k * 2;
-        const bool ok = (p < nk) && (cur.k + cl * 8 < kr.end(cur.run));
-#pragma unroll
-        for (int n = 0; n < N_LOADS; ++n) dma_n(n, a_base + kb, b0_base + kb, b1_base + kb, ok, p);
-        advance(cur);
+    // prologue: parts A0 B0 A1 B1 in flight, tile 0 landed
+    Issue qa, qb;
+    {
+        const KCursor c = k_seek(kr, kt_begin);
+        qa.run = c.run;
+        qa.k = c.k;
+        qa.kend = kr.end(c.run);
+        qa.left = nk;
+        qa.slot = 0;
+        qb = qa;
+        qb.slot = 1;
     }
-    pipeline_barrier<(NST - 2) * N_LOADS>();
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const Part pa = part_of(qa, a_base), pb = part_of(qb, b_base);
+#pragma unroll
+        for (int n = 0; n < PL; ++n) dma_part(n, pa, a_off);
+#pragma unroll
+        for (int n = 0; n < PL; ++n) dma_part(n, pb, b_off);
+        advance(qa);
+        advance(qb);
+    }
+    pipeline_barrier<2 * PL>();
     Frags f0, f1;
 #pragma unroll
     for (int g = 0; g < N_PIECES; ++g) read_piece(f0, g, 0, 0);
 
+    int rd = 0;                                   // ring slot of the A part of the tile in use
+    const Part none{nullptr, nullptr, {false, false}};
     for (int it = 0; it < nk; ++it) {
-        const int st = it & (NST - 1);
-        const size_t kb = (size_t)cur.k * 2;
-        const bool ok = (it + NST - 1 < nk) && (cur.k + cl * 8 < kr.end(cur.run));
-        k_step(f0, f1, st, 1, true, a_base + kb, b0_base + kb, b1_base + kb, ok, (it + NST - 1) & (NST - 1));
-        advance(cur);
-        pipeline_barrier<(NST - 2) * N_LOADS>();  // tile it+1 has landed; stage of tile it is free again
-        k_step(f1, f0, (it + 1) & (NST - 1), 0, false, nullptr, nullptr, nullptr, false, 0);
+        const Part pa = part_of(qa, a_base);
+        k_step(f0, f1, rd, 1, 1, pa);             // + A part of tile it+2
+        advance(qa);
+        k_step(f1, f0, rd, 2, 0, none);
+        k_step(f0, f1, rd, 3, 0, none);
+        pipeline_barrier<PL>();                   // tile it+1 has landed; tile it's slots are free
+        rd = rd + 2 < N_PARTS ? rd + 2 : rd + 2 - N_PARTS;
+        const Part pb = part_of(qb, b_base);
+        k_step(f1, f0, rd, 0, 2, pb);             // + B part of tile it+2
+        advance(qb);
     }
     pipeline_barrier<0>();                        // LDS may be reused by the caller
 }

@@ -109,11 +109,14 @@ __device__ __forceinline__ KCursor k_seek(const KR &kr, int tile)
 // are clamped to the last valid row: their results are never stored and MFMA rows / columns do
 // not mix.  K chunks past the end of a range are read from a zero chunk, in A and in B.
 // Schedule of K tile i (four K steps of 16; fragments are double buffered one step ahead):
-//   step 0: MFMAs; read step 1's fragments; issue the A part of tile i+2 (one load per slot)
-//   step 1, 2: MFMAs; read the next step's fragments
+//   step 0: MFMAs; read step 1's fragments; issue the second half of the B part of tile i+1
+//   step 1, 2: MFMAs; read the next step's fragments; issue one half each of the A part of tile i+2
 //   barrier: parts of tile i+1 have landed (only the newest A part may be in flight) and every
 //            wave has read its last fragments of tile i, whose two ring slots are free again
-//   step 3: MFMAs; read step 0's fragments of tile i+1; issue the B part of tile i+2
+//   step 3: MFMAs; read step 0's fragments of tile i+1; issue the first half of the B part of tile i+2
+// The direct loads are spread evenly over the steps (one per wave every other MFMA slot) because
+// a CU's vector memory path takes about as long to move a tile as the MFMAs take to consume it:
+// issued in bursts, the loads back up in the issue queue and the MFMAs behind them wait.
 template <int WM, typename KR>
 __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, int lda, int a_valid,
                                          const uint16_t *__restrict__ B0_tile,
@@ -126,7 +129,7 @@ __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, in
     constexpr int PL = 32 / NWAVES;               // 1 KiB wave-loads per wave per part: 8 or 4
     constexpr int N_SLOTS = MI * 2;               // slots of 2 MFMAs per K step
     constexpr int N_PIECES = 4 + MI;              // fragment pieces per K step
-    static_assert(PL == N_SLOTS, "one direct load per slot");
+    static_assert(PL == N_SLOTS, "one direct load every other slot, half a part per K step");
     const int nk = kt_end - kt_begin;
     if (nk <= 0) return;
     const int tid = threadIdx.x;
@@ -224,12 +227,13 @@ __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, in
         else acc0[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.v[4 + i], f.v[m & 3], acc0[i][j], 0, 0, 0);
     };
     // One K step, written in the instruction order wanted: slots of {2 MFMAs, then LDS reads of
-    // the next step's fragments, then one direct load (steps 0 and 3 only)}; nothing may be
+    // the next step's fragments, then (every other slot) one direct load}; nothing may be
     // moved across a slot boundary.  The compiler waits for ALL outstanding LDS reads before the
     // first MFMA of a step (direct-to-LDS loads in flight make it give up exact counting), so the
     // reads are packed into the early slots and the last slots leave them time to land.
-    // DMA: 0 none, 1 a load of the A part pt, 2 a load of the B part pt.
-    auto k_step = [&](const Frags &cur_f, Frags &nxt_f, int rd_slot, int rd_ks, int dma, const Part &pt) {
+    // DMA: 1 loads of the A part pt, 2 loads of the B part pt; half: which half of the part's loads.
+    auto k_step = [&](const Frags &cur_f, Frags &nxt_f, int rd_slot, int rd_ks, int dma, int half,
+                      const Part &pt) {
 #pragma unroll
         for (int g = 0; g < N_SLOTS; ++g) {
             mfma_n(cur_f, 2 * g);
@@ -248,13 +252,16 @@ __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, in
                     read_piece(nxt_f, 2 * g + 1, rd_slot, rd_ks);
                 }
             }
-            if (dma == 1) dma_part(g, pt, a_off);
-            if (dma == 2) dma_part(g, pt, b_off);
+            if ((g & 1) == 0) {
+                const int n = half * (PL / 2) + g / 2;
+                if (dma == 1) dma_part(n, pt, a_off);
+                if (dma == 2) dma_part(n, pt, b_off);
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
     };
 
-    // prologue: parts A0 B0 A1 B1 in flight, tile 0 landed
+    // prologue: parts A0 B0 A1 and the first half of B1 in flight, tile 0 landed
     Issue qa, qb;
     {
         const KCursor c = k_seek(kr, kt_begin);
@@ -266,34 +273,40 @@ __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, in
         qb = qa;
         qb.slot = 1;
     }
-#pragma unroll
-    for (int p = 0; p < 2; ++p) {
-        const Part pa = part_of(qa, a_base), pb = part_of(qb, b_base);
+    {
+        Part pa = part_of(qa, a_base), pb = part_of(qb, b_base);
 #pragma unroll
         for (int n = 0; n < PL; ++n) dma_part(n, pa, a_off);
 #pragma unroll
         for (int n = 0; n < PL; ++n) dma_part(n, pb, b_off);
         advance(qa);
         advance(qb);
+        pa = part_of(qa, a_base);
+        pb = part_of(qb, b_base);
+#pragma unroll
+        for (int n = 0; n < PL; ++n) dma_part(n, pa, a_off);
+#pragma unroll
+        for (int n = 0; n < PL / 2; ++n) dma_part(n, pb, b_off);
+        advance(qa);
     }
-    pipeline_barrier<2 * PL>();
+    pipeline_barrier<PL + PL / 2>();
     Frags f0, f1;
 #pragma unroll
     for (int g = 0; g < N_PIECES; ++g) read_piece(f0, g, 0, 0);
 
     int rd = 0;                                   // ring slot of the A part of the tile in use
-    const Part none{nullptr, nullptr, {false, false}};
     for (int it = 0; it < nk; ++it) {
+        Part pb = part_of(qb, b_base);
+        k_step(f0, f1, rd, 1, 2, 1, pb);          // + rest of the B part of tile it+1
+        advance(qb);
         const Part pa = part_of(qa, a_base);
-        k_step(f0, f1, rd, 1, 1, pa);             // + A part of tile it+2
+        k_step(f1, f0, rd, 2, 1, 0, pa);          // + A part of tile it+2
+        k_step(f0, f1, rd, 3, 1, 1, pa);
         advance(qa);
-        k_step(f1, f0, rd, 2, 0, none);
-        k_step(f0, f1, rd, 3, 0, none);
         pipeline_barrier<PL>();                   // tile it+1 has landed; tile it's slots are free
         rd = rd + 2 < N_PARTS ? rd + 2 : rd + 2 - N_PARTS;
-        const Part pb = part_of(qb, b_base);
-        k_step(f1, f0, rd, 0, 2, pb);             // + B part of tile it+2
-        advance(qb);
+        pb = part_of(qb, b_base);
+        k_step(f1, f0, rd, 0, 2, 0, pb);          // + start of the B part of tile it+2
     }
     pipeline_barrier<0>();                        // LDS may be reused by the caller
 }

@@ -15,6 +15,7 @@ the host cores for context.
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -27,6 +28,28 @@ sys.path.insert(0, ROOT)
 
 MFMA_PEAK_TFLOPS = 2516.6    # MI355X dense bf16: 256 CU x 2.4 GHz x 4096 flop/clk/CU
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
+
+# HBM traffic per launch of the dominant kernel, from two rocprofv3 --pmc runs of this script
+# (FETCH_SIZE, then WRITE_SIZE), scaled by what the same counters read for the elementwise pass of
+# --copy-mib.  Valid only for the kernel source it was measured on: keyed by that file's SHA-256,
+# and reported as null when the source has changed since.
+TRAFFIC = {
+    # (workload, kernel): (sha256 of the kernel's source file, bytes per launch)
+}
+KERNEL_SOURCE = {"gate_up_mfma": "kernels_mfma.hip", "down_mfma": "kernels_mfma.hip",
+                 "decode_gate_up": "kernels_decode.hip", "decode_down": "kernels_decode.hip"}
+
+
+def traffic_of(workload, kernel):
+    ent = TRAFFIC.get((workload, kernel))
+    src = KERNEL_SOURCE.get(kernel)
+    if ent is None or src is None:
+        return None
+    path = os.path.join(ROOT, "paper_2511_21089_amd", "csrc", src)
+    with open(path, "rb") as f:
+        if hashlib.sha256(f.read()).hexdigest() != ent[0]:
+            return None
+    return ent[1]
 
 
 def parse():
@@ -41,6 +64,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--copy-mib", type=int, default=0,
+                    help="before the timed steps, run one elementwise pass that reads and writes this many "
+                         "MiB (calibrates the HBM byte counters under rocprofv3 --pmc)")
     return ap.parse_args()
 
 
@@ -66,19 +92,31 @@ def build_layer(mm, synth, name, T, seed):
     return L, x, dev, host, off, alpha, mask, d_eff_alg
 
 
-def time_steps(mm, torch, call, steps, warmup):
-    """Warm up, then time exactly `steps` calls; returns (ms_per_step, {kernel: [ms...]})."""
+def time_steps(mm, torch, call, steps, warmup, events=True):
+    """Warm up, then time exactly `steps` calls; returns (ms_per_step, {kernel: [ms...]}).
+
+    With events=True the library brackets every kernel of the timed steps with HIP events on the
+    stream it launches on (about 3 us per kernel: fine for millisecond steps).  With events=False
+    the timed steps run bare and the per-kernel durations come from a second, untimed pass of the
+    same steps (used for the decode steps, where the events would be a tenth of the step).
+    """
     for i in range(warmup):
         call(i)
     torch.cuda.synchronize()
     cap = steps * 4
-    mm.mlpmoe_profile_enable(cap)
+    if events:
+        mm.mlpmoe_profile_enable(cap)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(steps):
         call(warmup + i)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    if not events:
+        mm.mlpmoe_profile_enable(cap)
+        for i in range(steps):
+            call(warmup + i)
+        torch.cuda.synchronize()
     per_kernel = {}
     for name, ms in mm.mlpmoe_profile_collect(cap):
         per_kernel.setdefault(name, []).append(ms)
@@ -86,7 +124,7 @@ def time_steps(mm, torch, call, steps, warmup):
     return (t1 - t0) * 1e3 / steps, per_kernel
 
 
-def roofline_of(per_kernel, T, d_model, d_eff, decode):
+def roofline_of(per_kernel, T, d_model, d_eff, decode, workload=None):
     """Roofline of the kernel with the largest total time."""
     if not per_kernel:
         return None
@@ -99,12 +137,12 @@ def roofline_of(per_kernel, T, d_model, d_eff, decode):
         io = T * d_model * 2 + T * d_eff * 2 if gate_up else T * d_eff * 2 + T * d_model * 4
         ach = (wbytes + io) / (avg_ms * 1e-3) / 1e9
         return {"kernel": dom, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,
+                "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": traffic_of(workload, dom),
                 "avg_kernel_us": round(avg_ms * 1e3, 2)}
     flops = (4.0 if gate_up else 2.0) * T * d_model * d_eff
     ach = flops / (avg_ms * 1e-3) / 1e12
     return {"kernel": dom, "bound": "mfma", "achieved": round(ach, 1), "peak": MFMA_PEAK_TFLOPS,
-            "unit": "TFLOP/s", "frac": round(ach / MFMA_PEAK_TFLOPS, 4), "traffic": None,
+            "unit": "TFLOP/s", "frac": round(ach / MFMA_PEAK_TFLOPS, 4), "traffic": traffic_of(workload, dom),
             "avg_kernel_us": round(avg_ms * 1e3, 2)}
 
 
@@ -156,7 +194,14 @@ def main():
         Wg, Wu, Wd = sets[i % len(sets)]
         mm.mlpmoe_forward_bf16(x, Wg, Wu, Wd, off, alpha, mask, out=out)
 
-    ms, per_kernel = time_steps(mm, torch, call, args.steps, args.warmup)
+    if args.copy_mib > 0:
+        src = torch.ones(args.copy_mib * (1 << 20) // 4, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.mul(src, 1.0, out=dst)              # reads copy_mib MiB, writes copy_mib MiB
+        torch.cuda.synchronize()
+        del src, dst
+
+    ms, per_kernel = time_steps(mm, torch, call, args.steps, args.warmup, events=not decode)
     result = {
         "metric": "MLP-layer tokens/s",
         "value": round(T / (ms * 1e-3), 1),
@@ -168,7 +213,7 @@ def main():
         "config": {"workload": "%s_T%d" % (args.workload, T), "d_model": d_model,
                    "d_inter": w.d_inter, "B": w.B, "d_eff": d_eff, "T": T,
                    "active_branches": int(mask.sum()), "weight_sets": len(sets)},
-        "roofline": roofline_of(per_kernel, T, d_model, d_eff, decode),
+        "roofline": roofline_of(per_kernel, T, d_model, d_eff, decode, "%s_T%d" % (args.workload, T)),
         "kernels_us": {k: round(1e3 * sum(v) / len(v), 2) for k, v in per_kernel.items()},
     }
     flops = 6.0 * T * d_model * d_eff
@@ -192,12 +237,12 @@ def main():
                 Wg, Wu, Wd = sets[i % len(sets)]
                 mm.mlpmoe_forward_bf16(xd, Wg, Wu, Wd, off, alpha, mask, out=outd)
 
-            msd, pk = time_steps(mm, torch, calld, 50, 10)
+            msd, pk = time_steps(mm, torch, calld, 50, 10, events=False)
             byts = 3 * d_model * d_eff * 2 + Td * d_model * 6
             dec["T%d" % Td] = {"tokens_per_s": round(Td / (msd * 1e-3), 1), "us_per_step": round(msd * 1e3, 2),
                                "gbs": round(byts / (msd * 1e-3) / 1e9, 1),
                                "hbm_frac": round(byts / (msd * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                               "roofline": roofline_of(pk, Td, d_model, d_eff, True),
+                               "roofline": roofline_of(pk, Td, d_model, d_eff, True, "%s_T%d" % (args.workload, Td)),
                                "kernels_us": {k: round(1e3 * sum(v) / len(v), 2) for k, v in pk.items()}}
         dec["weight_sets"] = len(sets)
         result["decode"] = dec

@@ -73,6 +73,14 @@ enum {
 MLPMOE_API const char *mlpmoe_status_string(int status);
 
 /*
+ * What the HIP runtime said when a call of THIS thread last returned MLPMOE_ERR_HIP: the failing
+ * runtime call or kernel launch and hipGetErrorString() of its code, e.g.
+ * "decode_down launch: invalid configuration argument".  Points into thread-local storage owned
+ * by the library (valid until the thread's next failing call); an empty string if none failed.
+ */
+MLPMOE_API const char *mlpmoe_last_error_detail(void);
+
+/*
  * mlpmoe_slice -- host only; touches no GPU.
  * Builds the branch table of one MLP (Sec. 3.1 slicing, Sec. 3.1 scalar gates,
  * Sec. 3.3 pruning rule).

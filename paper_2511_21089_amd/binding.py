@@ -22,7 +22,7 @@ ERR_NULL, ERR_SHAPE, ERR_OFFSETS, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, ERR_A
 PATH_AUTO, PATH_GENERIC, PATH_MFMA, PATH_DECODE = 0, 1, 2, 3
 MAX_BRANCHES = 64
 
-EXPORTS = ["mlpmoe_status_string", "mlpmoe_slice", "mlpmoe_compact", "mlpmoe_workspace_bytes",
+EXPORTS = ["mlpmoe_status_string", "mlpmoe_last_error_detail", "mlpmoe_slice", "mlpmoe_compact", "mlpmoe_workspace_bytes",
            "mlpmoe_forward_bf16", "mlpmoe_forward", "mlpmoe_forward_f32", "mlpmoe_forward_bf16_ws",
            "mlpmoe_forward_f32_ws", "mlpmoe_release", "mlpmoe_profile_enable",
            "mlpmoe_profile_collect", "mlpmoe_profile_disable"]
@@ -31,18 +31,31 @@ EXPORTS = ["mlpmoe_status_string", "mlpmoe_slice", "mlpmoe_compact", "mlpmoe_wor
 class MlpMoeError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
-        super().__init__("%s failed: %s (%d)" % (where, status_string(status), status))
+        detail = last_error_detail() if status == ERR_HIP else ""
+        super().__init__("%s failed: %s (%d)%s" % (where, status_string(status), status,
+                                                   " [" + detail + "]" if detail else ""))
 
 
 def _load() -> ctypes.CDLL:
     if not os.path.exists(LIB_PATH):
         # nothing built yet: build once (hipcc cross-compiles; no GPU needed)
         _build.build(force=True)
+    # The library and PyTorch must share ONE HIP runtime (device pointers and streams cross between
+    # them).  PyTorch ships its own libamdhip64 / libhsa-runtime64; loading it first makes the
+    # dynamic loader satisfy this library's libamdhip64.so.7 dependency with that same copy.  In
+    # the other order the system runtime would be loaded beside PyTorch's, and the one that
+    # initialises second reports "no ROCm-capable device".
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = ctypes.CDLL(LIB_PATH)
     vp, ip, fp, bp = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p
     i, sz = ctypes.c_int, ctypes.c_size_t
     lib.mlpmoe_status_string.argtypes = [i]
     lib.mlpmoe_status_string.restype = ctypes.c_char_p
+    lib.mlpmoe_last_error_detail.argtypes = []
+    lib.mlpmoe_last_error_detail.restype = ctypes.c_char_p
     lib.mlpmoe_slice.argtypes = [i, i, i, bp, i, ip, fp, bp, ip, i]
     lib.mlpmoe_slice.restype = i
     lib.mlpmoe_compact.argtypes = [vp, vp, vp, vp, i, i, i, i, vp, vp, vp, vp]
@@ -73,6 +86,11 @@ lib = _load()
 
 def status_string(status: int) -> str:
     return lib.mlpmoe_status_string(int(status)).decode()
+
+
+def last_error_detail() -> str:
+    """What the HIP runtime said when a call of this thread last failed with ERR_HIP ("" if none)."""
+    return lib.mlpmoe_last_error_detail().decode()
 
 
 def _check(status: int, where: str):

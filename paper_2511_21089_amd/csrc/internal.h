@@ -37,6 +37,19 @@ struct FwdArgs {
     hipStream_t stream;
 };
 
+extern thread_local char g_err_detail[192];
+
+// Records which runtime call failed and how (read back through mlpmoe_last_error_detail()).
+// Returns e, so that a failing site can `return note_hip_error("...", e);`.
+hipError_t note_hip_error(const char *where, hipError_t e);
+
+// Status of the launch just made; on failure notes `where` and hands the code back.
+inline hipError_t launch_status(const char *where)
+{
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? e : note_hip_error(where, e);
+}
+
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 

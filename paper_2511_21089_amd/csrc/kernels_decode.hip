@@ -350,13 +350,15 @@ hipError_t launch_decode_bf16(const FwdArgs &a, const BranchTable &bt)
         if (!attr_set) {
             int dev = 0;
             hipDeviceProp_t prop;
-            if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
-                return hipErrorUnknown;
+            hipError_t e = hipGetDevice(&dev);
+            if (e != hipSuccess) return note_hip_error("hipGetDevice", e);
+            e = hipGetDeviceProperties(&prop, dev);
+            if (e != hipSuccess) return note_hip_error("hipGetDeviceProperties", e);
             n_cus = prop.multiProcessorCount;
-            hipError_t e = hipFuncSetAttribute(
+            e = hipFuncSetAttribute(
                 reinterpret_cast<const void *>(&decode_gate_up_persist<MLPMOE_DEC_SNW, MLPMOE_DEC_SU>),
                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)kStreamLdsMax);
-            if (e != hipSuccess) return e;
+            if (e != hipSuccess) return note_hip_error("hipFuncSetAttribute(decode_gate_up_persist)", e);
             attr_set = true;
         }
         const int grid = tiles1 < n_cus ? (int)tiles1 : n_cus;
@@ -364,11 +366,13 @@ hipError_t launch_decode_bf16(const FwdArgs &a, const BranchTable &bt)
         decode_gate_up_persist<MLPMOE_DEC_SNW, MLPMOE_DEC_SU><<<grid, MLPMOE_DEC_SNW * 64, xs_bytes, a.stream>>>(
             X, a.T, static_cast<const uint16_t *>(a.Wg), static_cast<const uint16_t *>(a.Wu), a.d_model, H,
             a.ldh, (int)tiles1, bt);
+        if (launch_status("decode_gate_up_persist launch") != hipSuccess) return hipErrorLaunchFailure;
     } else {
         ProfileScope ps(MLPMOE_KERNEL_DECODE_GATE_UP, a.stream);
         decode_kernel<MLPMOE_DEC_NW1, MLPMOE_DEC_U1, true><<<(unsigned)tiles1, MLPMOE_DEC_NW1 * 64, 0, a.stream>>>(
             X, a.d_model, a.T, static_cast<const uint16_t *>(a.Wg), static_cast<const uint16_t *>(a.Wu),
             a.d_model, a.d_model, H, a.ldh, nullptr, bt);
+        if (launch_status("decode gate_up launch") != hipSuccess) return hipErrorLaunchFailure;
     }
     ProfileScope ps(MLPMOE_KERNEL_DECODE_DOWN, a.stream);
     if (tiles2 >= 192)
@@ -379,7 +383,7 @@ hipError_t launch_decode_bf16(const FwdArgs &a, const BranchTable &bt)
         decode_kernel<16, 4, false><<<tiles2, 1024, 0, a.stream>>>(
             H, a.ldh, a.T, static_cast<const uint16_t *>(a.Wd), nullptr, a.d_inter, a.d_model, nullptr,
             a.ldh, a.out, bt);
-    return hipGetLastError();
+    return launch_status("decode_down launch");
 }
 
 }  // namespace mlpmoe

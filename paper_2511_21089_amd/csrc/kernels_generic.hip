@@ -215,7 +215,7 @@ hipError_t compact_typed(const void *Wg, const void *Wu, const void *Wd, const i
             static_cast<const Tel *>(Wd) + (size_t)m0 * d_inter_src, gather,
             static_cast<Tel *>(Wd_c) + (size_t)m0 * n_rows, n_rows, d_inter_src);
     }
-    return hipGetLastError();
+    return launch_status("gather kernels launch");
 }
 
 template <typename TIn, typename TH>
@@ -234,7 +234,7 @@ hipError_t launch_generic_typed(const FwdArgs &a, const BranchTable &bt)
     down_generic<TIn, TH><<<g2, GTHREADS, 0, a.stream>>>(
         static_cast<const TH *>(a.H), static_cast<const TIn *>(a.Wd), a.out, a.T, a.d_model, a.d_inter,
         a.ldh, bt);
-    return hipGetLastError();
+    return launch_status("generic kernels launch");
 }
 
 }  // namespace
@@ -246,7 +246,7 @@ hipError_t launch_fill_zero(float *out, size_t n, hipStream_t s)
     if (blocks > 4096) blocks = 4096;
     ProfileScope ps(MLPMOE_KERNEL_FILL_ZERO, s);
     fill_zero_kernel<<<(unsigned)blocks, 256, 0, s>>>(out, n);
-    return hipGetLastError();
+    return launch_status("fill_zero launch");
 }
 
 hipError_t launch_generic(const FwdArgs &a, const BranchTable &bt, bool is_bf16)

@@ -521,6 +521,7 @@ hipError_t launch_mfma_bf16(const FwdArgs &a, const BranchTable &bt)
         static_cast<const uint16_t *>(a.x), static_cast<const uint16_t *>(a.Wg),
         static_cast<const uint16_t *>(a.Wu), static_cast<uint16_t *>(a.H), a.T, a.d_model, a.d_inter,
         a.ldh, tiles_m, (int)tiles_n1, bt);
+    if (launch_status("gate_up_mfma launch") != hipSuccess) return hipErrorLaunchFailure;
     }
     float *dst = splits > 1 ? a.partial : a.out;
     {
@@ -528,6 +529,7 @@ hipError_t launch_mfma_bf16(const FwdArgs &a, const BranchTable &bt)
     down_mfma<MFMA_WM><<<(unsigned)grid2, MFMA_WM * 128, 0, a.stream>>>(
         static_cast<const uint16_t *>(a.H), static_cast<const uint16_t *>(a.Wd), dst, a.T, a.d_model,
         a.d_inter, a.ldh, tiles_m, tiles_n2, splits, kt_total, bt);
+    if (launch_status("down_mfma launch") != hipSuccess) return hipErrorLaunchFailure;
     }
     if (splits > 1) {
         ProfileScope ps(MLPMOE_KERNEL_SPLITK_REDUCE, a.stream);
@@ -536,7 +538,7 @@ hipError_t launch_mfma_bf16(const FwdArgs &a, const BranchTable &bt)
         if (blocks > 8192) blocks = 8192;
         reduce_partials<<<(unsigned)blocks, 256, 0, a.stream>>>(a.partial, a.out, n, splits);
     }
-    return hipGetLastError();
+    return launch_status("reduce_partials launch");
 }
 
 }  // namespace mlpmoe

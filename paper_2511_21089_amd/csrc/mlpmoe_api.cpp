@@ -2,6 +2,7 @@
 // table, workspace management and kernel-path dispatch.  No arithmetic of the
 // forward itself lives here.
 #include <math.h>
+#include <stdio.h>
 #include <string.h>
 
 #include <map>
@@ -105,6 +106,7 @@ int forward_impl(const void *x, const void *Wg, const void *Wu, const void *Wd, 
     // launch status is read back with hipGetLastError(): drop whatever an earlier, unrelated
     // runtime call of this thread left behind (e.g. a "not ready" from an event query)
     (void)hipGetLastError();
+    g_err_detail[0] = 0;
 
     if (bt.n_runs == 0) {   // nothing active: the sum over branches is empty
         return launch_fill_zero(out, (size_t)T * d_model, stream) == hipSuccess ? MLPMOE_OK
@@ -137,6 +139,7 @@ int forward_impl(const void *x, const void *Wg, const void *Wu, const void *Wd, 
     if (path == MLPMOE_PATH_GENERIC) e = launch_generic(a, bt, is_bf16);
     else if (path == MLPMOE_PATH_MFMA) e = launch_mfma_bf16(a, bt);
     else e = launch_decode_bf16(a, bt);
+    if (e != hipSuccess && g_err_detail[0] == 0) (void)note_hip_error("kernel launch", e);
     return e == hipSuccess ? MLPMOE_OK : MLPMOE_ERR_HIP;
 }
 
@@ -144,12 +147,20 @@ int forward_impl(const void *x, const void *Wg, const void *Wu, const void *Wd, 
 int owned_workspace(size_t need, void **ptr, size_t *bytes)
 {
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return MLPMOE_ERR_HIP;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) {
+        (void)note_hip_error("hipGetDevice", e);
+        return MLPMOE_ERR_HIP;
+    }
     std::lock_guard<std::mutex> lock(g_ws_mutex);
     DeviceWorkspace &w = g_ws[dev];
     if (w.bytes < need) {
         if (w.ptr) {
-            if (hipDeviceSynchronize() != hipSuccess) return MLPMOE_ERR_HIP;
+            e = hipDeviceSynchronize();      // earlier launches may still be using the old block
+            if (e != hipSuccess) {
+                (void)note_hip_error("hipDeviceSynchronize before growing the workspace", e);
+                return MLPMOE_ERR_HIP;
+            }
             (void)hipFree(w.ptr);
             w.ptr = nullptr;
             w.bytes = 0;
@@ -186,6 +197,14 @@ int forward_owned(const void *x, const void *Wg, const void *Wu, const void *Wd,
 }  // namespace
 
 namespace mlpmoe {
+thread_local char g_err_detail[192] = "";
+
+hipError_t note_hip_error(const char *where, hipError_t e)
+{
+    snprintf(g_err_detail, sizeof(g_err_detail), "%s: %s", where, hipGetErrorString(e));
+    return e;
+}
+
 void profile_mark(int kernel_id, hipStream_t s, bool begin)
 {
     if (!g_prof.on) return;
@@ -241,6 +260,8 @@ int mlpmoe_profile_collect(int *ids, float *ms, int capacity)
     g_prof.count = 0;
     return n;
 }
+
+const char *mlpmoe_last_error_detail(void) { return mlpmoe::g_err_detail; }
 
 const char *mlpmoe_status_string(int status)
 {

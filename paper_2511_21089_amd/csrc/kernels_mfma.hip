@@ -19,6 +19,8 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 constexpr int BM = 256;          // tokens per tile
 constexpr int BNH = 128;         // rows of each of the two B blocks
@@ -117,7 +119,7 @@ __device__ __forceinline__ KCursor k_seek(const KR &kr, int tile)
 // The direct loads are spread evenly over the steps (one per wave every other MFMA slot) because
 // a CU's vector memory path takes about as long to move a tile as the MFMAs take to consume it:
 // issued in bursts, the loads back up in the issue queue and the MFMAs behind them wait.
-template <int WM, typename KR>
+template <int WM, bool kRowsAreB, typename KR>
 __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, int lda, int a_valid,
                                          const uint16_t *__restrict__ B0_tile,
                                          const uint16_t *__restrict__ B1_tile, int ldb, int b0_valid,
@@ -221,10 +223,17 @@ __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, in
         else
             f.v[g] = *reinterpret_cast<const bf16x8 *>(lds + a_slot * PART_BYTES + a_rd[ks] + (g - 4) * (32 * 128));
     };
+    // kRowsAreB: the B rows (weights) are the MFMA's row operand and the A rows (tokens) its column
+    // operand.  In the 32x32 result lane l then holds column l % 32 = one token and, in registers
+    // 4g .. 4g+3, rows 8g + 4 * (l / 32) + 0..3 = four consecutive neurons, which the gate+up
+    // epilogue turns into one 8-byte piece of the token's row of H.  Otherwise tokens are the rows
+    // and a lane holds one B row for 16 tokens (the down projection: 32 lanes store 128
+    // contiguous bytes of fp32 per token).
     auto mfma_n = [&](const Frags &f, int m) {
         const int i = m >> 2, j = (m >> 1) & 1;
-        if (m & 1) acc1[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.v[4 + i], f.v[m & 3], acc1[i][j], 0, 0, 0);
-        else acc0[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.v[4 + i], f.v[m & 3], acc0[i][j], 0, 0, 0);
+        const bf16x8 r = kRowsAreB ? f.v[m & 3] : f.v[4 + i], c = kRowsAreB ? f.v[4 + i] : f.v[m & 3];
+        if (m & 1) acc1[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(r, c, acc1[i][j], 0, 0, 0);
+        else acc0[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(r, c, acc0[i][j], 0, 0, 0);
     };
     // One K step, written in the instruction order wanted: slots of {2 MFMAs, then LDS reads of
     // the next step's fragments, then (every other slot) one direct load}; nothing may be
@@ -389,23 +398,41 @@ gate_up_mfma(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
             }
 
     const int nk = (d_model + BK - 1) / BK;
-    mainloop<WM>(X + (size_t)t0 * d_model, d_model, T - t0, Wg + (size_t)n0 * d_model,
+    mainloop<WM, true>(X + (size_t)t0 * d_model, d_model, T - t0, Wg + (size_t)n0 * d_model,
              Wu + (size_t)n0 * d_model, d_model, n_end - n0, n_end - n0, KSingle{d_model}, 0, nk, lds,
              accg, accu);
 
+    // alpha of the tile's 128 neurons -> LDS (the main loop is done with it)
+    float *al = reinterpret_cast<float *>(lds);
+    if (threadIdx.x < BNH) {
+        const int n = n0 + threadIdx.x;
+        al[threadIdx.x] = n < n_end ? bt.alpha[branch_of(bt, n)] : 0.f;
+    }
+    __syncthreads();
+
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave >> 1, wn = wave & 1;
+    const int tcol = lane & 31, hi = lane >> 5;
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int n = n0 + wn * 64 + j * 32 + (lane & 31);
-        if (n >= n_end) continue;
-        const float al = bt.alpha[branch_of(bt, n)];
+    for (int i = 0; i < MI; ++i) {
+        const int t = t0 + wm * (MI * 32) + i * 32 + tcol;
 #pragma unroll
-        for (int i = 0; i < MI; ++i) {
+        for (int j = 0; j < 2; ++j) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int t = t0 + wm * (MI * 32) + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                if (t < T) H[(size_t)t * ldh + n] = to_bf16(al * silu_mul(accg[i][j][v], accu[i][j][v]));
+            for (int g = 0; g < 4; ++g) {
+                const int nl = wn * 64 + j * 32 + 8 * g + 4 * hi;     // first of 4 neurons, tile relative
+                // run ends are multiples of 8: the four neurons are all inside the run or all outside
+                if (t < T && n0 + nl < n_end) {
+                    const f32x4 a4 = *reinterpret_cast<const f32x4 *>(al + nl);
+                    uint16_t h[4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        h[q] = to_bf16(a4[q] * silu_mul(accg[i][j][4 * g + q], accu[i][j][4 * g + q]));
+                    u32x2 pk;
+                    pk.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
+                    pk.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
+                    *reinterpret_cast<u32x2 *>(H + (size_t)t * ldh + n0 + nl) = pk;
+                }
             }
         }
     }
@@ -441,7 +468,7 @@ down_mfma(const uint16_t *__restrict__ H, const uint16_t *__restrict__ Wd, float
 
     // the second block of 128 output features may start past d_model: point it at the last row
     const int n1 = n0 + BNH < d_model ? n0 + BNH : d_model - 1;
-    mainloop<WM>(H + (size_t)t0 * ldh, ldh, T - t0, Wd + (size_t)n0 * d_inter, Wd + (size_t)n1 * d_inter,
+    mainloop<WM, false>(H + (size_t)t0 * ldh, ldh, T - t0, Wd + (size_t)n0 * d_inter, Wd + (size_t)n1 * d_inter,
              d_inter, d_model - n0, d_model - n1, KRuns{bt}, kt_begin, kt_end, lds, acc0, acc1);
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;

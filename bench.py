@@ -63,6 +63,8 @@ def parse():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-others", action="store_true",
+                    help="skip the short runs of the other workloads (0.5B-shaped layer, pruned and faded layers)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--copy-mib", type=int, default=0,
                     help="before the timed steps, run one elementwise pass that reads and writes this many "
@@ -166,6 +168,42 @@ def cpu_baseline(synth, L, host, off, alpha, mask, seconds):
             "sample": "first %d of %d tokens of the same batch, exact fp64 mode, %.1f s" % (n, L.T, dt)}
 
 
+def others(mm, synth, torch, seed):
+    """Short runs of the remaining workloads: tokens/s and the fraction of the roofline that bounds them."""
+    res = {}
+    for name, Ts in (("qwen05b", (2048, 1)), ("qwen05b_pruned", (2048, 16, 1)), ("llama8b_fade", (4096, 16, 1)),
+                     ("llama8b", (512,))):
+        Tmax = max(Ts)
+        L, x, dev, _, off, alpha, mask, d_eff = build_layer(mm, synth, name, Tmax, seed)
+        w = L.workload
+        wbytes = 3 * w.d_model * int(off[-1]) * 2
+        for T in Ts:
+            decode = T <= 16
+            n_sets = max(2, int(np.ceil(2 * 256e6 / wbytes))) if decode else 1
+            sets = [dev] + [[t.clone() for t in dev] for _ in range(n_sets - 1)]
+            xT = x[:T].contiguous()
+            out = torch.empty((T, w.d_model), dtype=torch.float32, device="cuda")
+
+            def call(i, xT=xT, out=out, sets=sets):
+                Wg, Wu, Wd = sets[i % len(sets)]
+                mm.mlpmoe_forward_bf16(xT, Wg, Wu, Wd, off, alpha, mask, out=out)
+
+            ms, pk = time_steps(mm, torch, call, 50 if decode else 20, 10 if decode else 5, events=False)
+            ent = {"tokens_per_s": round(T / (ms * 1e-3), 1), "us_per_step": round(ms * 1e3, 2), "d_eff": d_eff,
+                   "kernels_us": {k: round(1e3 * sum(v) / len(v), 2) for k, v in pk.items()}}
+            if decode:
+                byts = 3 * w.d_model * d_eff * 2 + T * w.d_model * 6
+                ent["hbm_frac"] = round(byts / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+                ent["weight_sets"] = len(sets)
+            else:
+                ent["mfma_frac"] = round(6.0 * T * w.d_model * d_eff / (ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS, 4)
+            res["%s_T%d" % (name, T)] = ent
+            del sets, out
+        del x, dev
+        torch.cuda.empty_cache()
+    return res
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -247,6 +285,11 @@ def main():
         dec["weight_sets"] = len(sets)
         result["decode"] = dec
         del sets
+
+    if not args.no_others and args.workload == "llama8b" and T == 4096:
+        # context: the other configurations, a few steps each (same code path, same timing rules)
+        del x, dev, out
+        result["other_workloads"] = others(mm, synth, torch, args.seed)
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(synth, L, host, off, alpha, mask, args.cpu_seconds)

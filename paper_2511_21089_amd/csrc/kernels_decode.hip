@@ -209,28 +209,6 @@ decode_gate_up_persist(const uint16_t *__restrict__ X, int T, const uint16_t *__
     char *xs = smem + 2 * NW * 256 * sizeof(float);
     const int row_bytes = d_model * 2 + 16;
     const int zero_off = T * row_bytes;                  // 16 zero bytes after the last row
-    {
-        const int chunks = T * (d_model / 8);            // 16-byte chunks of x
-        for (int i0 = 0; i0 < chunks; i0 += NW * 64 * 8) {
-            u32x4 v[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {                // 8 loads in flight per thread
-                const int i = i0 + j * (NW * 64) + threadIdx.x;
-                v[j] = ld16(i < chunks ? X + (size_t)i * 8 : reinterpret_cast<const uint16_t *>(g_zero16));
-            }
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int i = i0 + j * (NW * 64) + threadIdx.x;
-                if (i < chunks) {
-                    const int t = i / (d_model / 8), c = i % (d_model / 8);
-                    *reinterpret_cast<u32x4 *>(xs + t * row_bytes + c * 16) = v[j];
-                }
-            }
-        }
-    }
-    if (threadIdx.x == 0) *reinterpret_cast<u32x4 *>(xs + zero_off) = u32x4{0, 0, 0, 0};
-    __syncthreads();
-
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int r16 = lane & 15, q = lane >> 4;
@@ -269,7 +247,30 @@ decode_gate_up_persist(const uint16_t *__restrict__ X, int T, const uint16_t *__
         }
     };
 #pragma unroll
-    for (int u = 0; u < U; ++u) load_next(u);
+    for (int u = 0; u < U; ++u) load_next(u);            // the weight stream starts before x is staged
+
+    // x -> LDS, while the first weight blocks are on their way
+    {
+        const int chunks = T * (d_model / 8);            // 16-byte chunks of x
+        for (int i0 = 0; i0 < chunks; i0 += NW * 64 * 8) {
+            u32x4 v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {                // 8 loads in flight per thread
+                const int i = i0 + j * (NW * 64) + threadIdx.x;
+                v[j] = ld16(i < chunks ? X + (size_t)i * 8 : reinterpret_cast<const uint16_t *>(g_zero16));
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int i = i0 + j * (NW * 64) + threadIdx.x;
+                if (i < chunks) {
+                    const int t = i / (d_model / 8), c = i % (d_model / 8);
+                    *reinterpret_cast<u32x4 *>(xs + t * row_bytes + c * 16) = v[j];
+                }
+            }
+        }
+    }
+    if (threadIdx.x == 0) *reinterpret_cast<u32x4 *>(xs + zero_off) = u32x4{0, 0, 0, 0};
+    __syncthreads();
 
     int it = 0;
     for (int tile = blockIdx.x; tile < tiles; tile += gridDim.x, ++it) {

@@ -34,7 +34,12 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 # --copy-mib.  Valid only for the kernel source it was measured on: keyed by that file's SHA-256,
 # and reported as null when the source has changed since.
 TRAFFIC = {
-    # (workload, kernel): (sha256 of the kernel's source file, bytes per launch)
+    # (workload, kernel): (sha256 of the kernel's source file, bytes per launch = read + written)
+    # gate_up_mfma at T=4096: 1409.4 MB read (x is re-read once per group of 4 neuron tiles and the
+    # weights once per XCD that needs them: 5.3x the 268 MB the kernel has to read) + 119.1 MB written
+    ("llama8b_T4096", "gate_up_mfma"): ("6a9d908a34ae306c6d7be04cc50dfeb7e30c5f8e92061030f1f62d7753b381de", 1528.5e6),
+    # decode gate+up at T=1: 235.1 MB read (the weights, once) + 0.1 MB written
+    ("llama8b_T1", "decode_gate_up"): ("3307daf5ad802fac2e17db738481aa389b3c27353e134cb985be7ab679dc84ea", 235.2e6),
 }
 KERNEL_SOURCE = {"gate_up_mfma": "kernels_mfma.hip", "down_mfma": "kernels_mfma.hip",
                  "decode_gate_up": "kernels_decode.hip", "decode_down": "kernels_decode.hip"}

@@ -204,6 +204,27 @@ def others(mm, synth, torch, seed):
                 ent["mfma_frac"] = round(6.0 * T * w.d_model * d_eff / (ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS, 4)
             res["%s_T%d" % (name, T)] = ent
             del sets, out
+        if name == "llama8b":
+            # Sec. 3.3 swept over K on the same weights: keep the first K of 16 branches, alpha = sqrt(16/K)
+            sweep = {}
+            xs = mm.bf16_tensor(synth.make_layer(name, 4096, seed=seed).x)
+            sets = [dev, [t.clone() for t in dev]]
+            for K in (4, 8, 12, 16):
+                offk, alphak, maskk, _ = mm.mlpmoe_slice(w.d_inter, w.B, K)
+                row = {}
+                for T in (4096, 1):
+                    xT = xs[:T].contiguous()
+                    out = torch.empty((T, w.d_model), dtype=torch.float32, device="cuda")
+
+                    def callk(i, xT=xT, out=out):
+                        Wg, Wu, Wd = sets[i % 2]
+                        mm.mlpmoe_forward_bf16(xT, Wg, Wu, Wd, offk, alphak, maskk, out=out)
+
+                    ms, _ = time_steps(mm, torch, callk, 20 if T > 16 else 50, 5, events=False)
+                    row["T%d_us" % T] = round(ms * 1e3, 2)
+                sweep["K%d" % K] = row
+            res["llama8b_first_k_sweep"] = sweep
+            del sets, xs
         del x, dev
         torch.cuda.empty_cache()
     return res

@@ -226,3 +226,58 @@ def test_compensated_pruning_first_k(mm):
     check_bf16(run_gpu(*args, path=mm.PATH_MFMA), args)
     a16 = (L.x[:16],) + args[1:]
     check_bf16(run_gpu(*a16, path=mm.PATH_DECODE), a16)
+
+
+# ------------------------------------------------------------------ other branch counts and uneven splits
+@pytest.mark.parametrize("B,pruned", [(4, [2]), (32, [0, 5, 6, 7, 31])])
+def test_branch_counts_4_and_32(mm, B, pruned):
+    """The 0.5B-shaped layer cut into B = 4 and B = 32 branches (the other branch counts of Sec. 4)."""
+    L = synth.make_layer("qwen05b", 300, seed=B, B=B)
+    off, _, mask, _ = mm.mlpmoe_slice(4864, B)
+    mask[pruned] = 0
+    alpha = np.random.default_rng(B).uniform(0.9, 1.2, size=B).astype(np.float32)
+    args = (L.x, L.W_gate, L.W_up, L.W_down, off, alpha, mask)
+    check_bf16(run_gpu(*args), args)                       # T = 300: MFMA kernels
+    a7 = (L.x[:7],) + args[1:]
+    check_bf16(run_gpu(*a7), a7)                           # T = 7: decode kernels
+
+
+def test_d_inter_not_divisible_by_B(mm):
+    """d_inter = 4870 over B = 8: the first 6 branches are one neuron wider (609, 608).  The raw table
+    has unaligned boundaries (generic kernels); padded to multiples of 8 and compacted it takes the
+    MFMA and decode kernels.  All three must match the oracle on the original layer."""
+    d_inter, B = 4870, 8
+    L = synth.make_layer("qwen05b", 130, seed=9, d_inter=d_inter)
+    off, _, mask, _ = mm.mlpmoe_slice(d_inter, B)
+    assert list(np.diff(off)) == [609] * 6 + [608] * 2
+    mask[3] = 0
+    alpha = L.alpha_draw
+    args = (L.x, L.W_gate, L.W_up, L.W_down, off, alpha, mask)
+    check_bf16(run_gpu(*args), args)                       # unaligned: generic kernels
+    keep = np.ones(d_inter, np.uint8)
+    off8, _, _, gather = mm.mlpmoe_slice(d_inter, B, 0, keep, pad_to=8)
+    assert all(int(o) % 8 == 0 for o in off8) and int(off8[-1]) == 6 * 616 + 2 * 608
+    dev = tuple(to_dev(a) for a in (L.W_gate, L.W_up, L.W_down))
+    Wc = mm.mlpmoe_compact(dev[0], dev[1], dev[2], gather)
+    x_d = to_dev(L.x)
+    out = mm.mlpmoe_forward_bf16(x_d, Wc[0], Wc[1], Wc[2], off8, alpha, mask)
+    check_bf16(out.cpu().numpy(), args)                    # T = 130: MFMA kernels
+    out = mm.mlpmoe_forward_bf16(x_d[:16], Wc[0], Wc[1], Wc[2], off8, alpha, mask)
+    check_bf16(out.cpu().numpy(), (L.x[:16],) + args[1:])  # decode kernels
+
+
+@pytest.mark.parametrize("K", [1, 3, 8])
+def test_first_k_sweep(mm, K):
+    """Sec. 3.3 for several K on the 0.5B-shaped layer: alpha = sqrt(B / K), branches K.. skipped."""
+    L = synth.make_layer("qwen05b", 64, seed=20 + K)
+    off, alpha, mask, _ = mm.mlpmoe_slice(4864, 8, K_keep=K)
+    assert np.allclose(alpha[:K], np.sqrt(8.0 / K)) and mask.sum() == K
+    args = (L.x, L.W_gate, L.W_up, L.W_down, off, alpha, mask)
+    if K * 608 >= 1000:                                    # see check_bf16: enough active neurons
+        check_bf16(run_gpu(*args), args)
+    else:
+        got = run_gpu(*args)
+        assert oracle.rel_max_err(got, oracle_out(*args, "exact")) <= BF16_TOL
+    a1 = (L.x[:1],) + args[1:]
+    got = run_gpu(*a1)
+    assert oracle.rel_max_err(got, oracle_out(*a1, "exact")) <= BF16_TOL

@@ -192,6 +192,33 @@ MLPMOE_API int mlpmoe_forward_f32_ws(const float *x, const float *W_gate, const 
                           float *out, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * mlpmoe_fade -- Fractal Fade weight preparation (Sec. 3.2), in place, on the device.
+ *
+ * For every branch b with sparsity[b] > 0, and separately for the branch's rows of W_gate and of
+ * W_up (row-major [d_inter, d_model]; W_down is not touched): take the linear-interpolation
+ * quantile of the absolute values of that block at fraction sparsity[b] (position
+ * p = s (n - 1) in the ascending order statistics, n = d_b * d_model) and set every entry whose
+ * absolute value is not strictly greater than it to zero (the entry times 0: it keeps its sign).
+ * Branches with sparsity[b] <= 0, and empty branches, are left exactly as they are.
+ *
+ *   W_gate, W_up    device, bf16 (elem_bytes must be 2; MLPMOE_ERR_UNSUPPORTED otherwise),
+ *                   16-byte aligned; d_model must be a multiple of 8 (MLPMOE_ERR_UNSUPPORTED)
+ *   branch_offsets  host, B + 1 entries as for mlpmoe_forward
+ *   sparsity        host, B doubles in [0, 1] (MLPMOE_ERR_SHAPE outside), or NULL for the
+ *                   schedule of Sec. 3.2: s_b = 0.9 * b / B, branch 0 dense
+ *   thresholds      host, 2 * B floats or NULL: [2b] gate, [2b+1] up; the interpolated quantile
+ *                   (NaN for branches left alone)
+ *   kept            host, 2 * B 64-bit counts or NULL: entries of the block that survive
+ *                   (the block size for branches left alone)
+ * Allocates and frees a device scratch buffer of B * 131088 bytes and synchronises `stream`
+ * before it returns (this is offline weight preparation, not part of the forward).
+ * Not-a-number entries are not supported (their place in the order is undefined).
+ */
+MLPMOE_API int mlpmoe_fade(void *W_gate, void *W_up, const int32_t *branch_offsets, const double *sparsity,
+                           int d_model, int d_inter, int B, int elem_bytes, float *thresholds,
+                           long long *kept, void *stream);
+
+/*
  * Per-kernel timing (measurement aid; the arithmetic is unchanged and nothing is skipped).
  * While enabled, every kernel a forward call launches is bracketed by a pair of HIP events
  * recorded on the call's own stream.

@@ -22,7 +22,7 @@ ERR_NULL, ERR_SHAPE, ERR_OFFSETS, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, ERR_A
 PATH_AUTO, PATH_GENERIC, PATH_MFMA, PATH_DECODE = 0, 1, 2, 3
 MAX_BRANCHES = 64
 
-EXPORTS = ["mlpmoe_status_string", "mlpmoe_last_error_detail", "mlpmoe_slice", "mlpmoe_compact", "mlpmoe_workspace_bytes",
+EXPORTS = ["mlpmoe_status_string", "mlpmoe_last_error_detail", "mlpmoe_slice", "mlpmoe_compact", "mlpmoe_fade", "mlpmoe_workspace_bytes",
            "mlpmoe_forward_bf16", "mlpmoe_forward", "mlpmoe_forward_f32", "mlpmoe_forward_bf16_ws",
            "mlpmoe_forward_f32_ws", "mlpmoe_release", "mlpmoe_profile_enable",
            "mlpmoe_profile_collect", "mlpmoe_profile_disable"]
@@ -60,6 +60,8 @@ def _load() -> ctypes.CDLL:
     lib.mlpmoe_slice.restype = i
     lib.mlpmoe_compact.argtypes = [vp, vp, vp, vp, i, i, i, i, vp, vp, vp, vp]
     lib.mlpmoe_compact.restype = i
+    lib.mlpmoe_fade.argtypes = [vp, vp, ip, vp, i, i, i, i, vp, vp, vp]
+    lib.mlpmoe_fade.restype = i
     lib.mlpmoe_workspace_bytes.argtypes = [i, i, i, i, i]
     lib.mlpmoe_workspace_bytes.restype = sz
     fwd = [vp, vp, vp, vp, ip, fp, bp, i, i, i, i, vp, vp]
@@ -155,6 +157,28 @@ def mlpmoe_compact(W_gate, W_up, W_down, gather_index, stream=None):
                             _dev_ptr(Wg_c), _dev_ptr(Wu_c), _dev_ptr(Wd_c), _stream_ptr(stream))
     _check(rc, "mlpmoe_compact")
     return Wg_c, Wu_c, Wd_c
+
+
+def mlpmoe_fade(W_gate, W_up, branch_offsets, sparsity=None, stream=None):
+    """Fractal Fade (Sec. 3.2) of W_gate and W_up in place on the device.
+
+    Returns (thresholds [B, 2] float32 with NaN for untouched branches, kept [B, 2] int64).
+    """
+    off = _host(branch_offsets, np.int32)
+    B = off.shape[0] - 1
+    d_inter, d_model = W_gate.shape
+    sp = None
+    if sparsity is not None:
+        sp = np.ascontiguousarray(sparsity, dtype=np.float64)
+        if sp.shape != (B,):
+            raise ValueError("sparsity needs B entries")
+    thr = np.zeros((B, 2), dtype=np.float32)
+    kept = np.zeros((B, 2), dtype=np.int64)
+    rc = lib.mlpmoe_fade(_dev_ptr(W_gate), _dev_ptr(W_up), off.ctypes.data,
+                         sp.ctypes.data if sp is not None else None, int(d_model), int(d_inter), int(B),
+                         int(W_gate.element_size()), thr.ctypes.data, kept.ctypes.data, _stream_ptr(stream))
+    _check(rc, "mlpmoe_fade")
+    return thr, kept
 
 
 def _table(branch_offsets, alpha, active_mask):

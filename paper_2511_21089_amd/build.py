@@ -15,7 +15,8 @@ CSRC = os.path.join(PKG_DIR, "csrc")
 BUILD_DIR = os.path.join(PKG_DIR, "_build")
 LIB_PATH = os.path.join(PKG_DIR, "libmlpmoe.so")
 
-SOURCES = ["mlpmoe_api.cpp", "kernels_generic.hip", "kernels_mfma.hip", "kernels_decode.hip"]
+SOURCES = ["mlpmoe_api.cpp", "kernels_generic.hip", "kernels_mfma.hip", "kernels_decode.hip",
+           "kernels_fade.hip"]
 HEADERS = [os.path.join(CSRC, "internal.h"), os.path.join(ROOT, "include", "mlpmoe.h")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

@@ -39,6 +39,11 @@ struct FwdArgs {
 
 extern thread_local char g_err_detail[192];
 
+// Fractal Fade of one bf16 projection matrix (see kernels_fade.hip); synchronises the stream.
+hipError_t launch_fade_bf16(void *W, const int32_t *off, const double *sparsity, int B, int d_model,
+                            uint32_t *scratch, uint32_t *host_result, int *job_of_branch, hipStream_t s);
+size_t fade_scratch_words(int B);
+
 // Records which runtime call failed and how (read back through mlpmoe_last_error_detail()).
 // Returns e, so that a failing site can `return note_hip_error("...", e);`.
 hipError_t note_hip_error(const char *where, hipError_t e);

@@ -324,6 +324,66 @@ int mlpmoe_slice(int d_inter, int B, int K_keep, const uint8_t *neuron_keep, int
     return MLPMOE_OK;
 }
 
+int mlpmoe_fade(void *W_gate, void *W_up, const int32_t *branch_offsets, const double *sparsity, int d_model,
+                int d_inter, int B, int elem_bytes, float *thresholds, long long *kept, void *stream)
+{
+    if (B < 1 || B > MLPMOE_MAX_BRANCHES || d_model < 1 || d_inter < 0) return MLPMOE_ERR_SHAPE;
+    if (!branch_offsets) return MLPMOE_ERR_NULL;
+    if (branch_offsets[0] != 0 || branch_offsets[B] != d_inter) return MLPMOE_ERR_OFFSETS;
+    for (int b = 0; b < B; ++b)
+        if (branch_offsets[b + 1] < branch_offsets[b]) return MLPMOE_ERR_OFFSETS;
+    double sched[MLPMOE_MAX_BRANCHES];
+    for (int b = 0; b < B; ++b) {
+        sched[b] = sparsity ? sparsity[b] : 0.9 * (double)b / (double)B;
+        if (!(sched[b] >= 0.0 && sched[b] <= 1.0)) return MLPMOE_ERR_SHAPE;
+    }
+    for (int b = 0; b < B; ++b) {
+        if (thresholds) thresholds[2 * b] = thresholds[2 * b + 1] = NAN;
+        if (kept) kept[2 * b] = kept[2 * b + 1] = (long long)(branch_offsets[b + 1] - branch_offsets[b]) * d_model;
+    }
+    if (d_inter == 0) return MLPMOE_OK;
+    if (!W_gate || !W_up) return MLPMOE_ERR_NULL;
+    if (elem_bytes != 2 || d_model % 8 != 0) return MLPMOE_ERR_UNSUPPORTED;
+    if (!aligned16(W_gate) || !aligned16(W_up)) return MLPMOE_ERR_ALIGN;
+
+    (void)hipGetLastError();
+    g_err_detail[0] = 0;
+    uint32_t *scratch = nullptr;
+    hipError_t e = hipMalloc(reinterpret_cast<void **>(&scratch), fade_scratch_words(B) * sizeof(uint32_t));
+    if (e != hipSuccess) {
+        (void)note_hip_error("hipMalloc(fade scratch)", e);
+        (void)hipGetLastError();
+        return MLPMOE_ERR_HIP;
+    }
+    int rc = MLPMOE_OK;
+    void *mats[2] = {W_gate, W_up};
+    for (int m = 0; m < 2 && rc == MLPMOE_OK; ++m) {
+        uint32_t res[4 * MLPMOE_MAX_BRANCHES];
+        int job[MLPMOE_MAX_BRANCHES];
+        e = launch_fade_bf16(mats[m], branch_offsets, sched, B, d_model, scratch, res, job,
+                             static_cast<hipStream_t>(stream));
+        if (e != hipSuccess) {
+            rc = MLPMOE_ERR_HIP;
+            break;
+        }
+        for (int b = 0; b < B; ++b) {
+            const int j = job[b];
+            if (j < 0) continue;
+            const long long n = (long long)(branch_offsets[b + 1] - branch_offsets[b]) * d_model;
+            const double p = sched[b] * (double)(n - 1);
+            const double frac = p - (double)(long long)p;
+            const uint32_t lo_bits = res[4 * j] << 16, hi_bits = res[4 * j + 1] << 16;
+            float lo, hi;
+            memcpy(&lo, &lo_bits, 4);
+            memcpy(&hi, &hi_bits, 4);
+            if (thresholds) thresholds[2 * b + m] = (float)((double)lo + frac * ((double)hi - (double)lo));
+            if (kept) kept[2 * b + m] = (long long)(((unsigned long long)res[4 * j + 3] << 32) | res[4 * j + 2]);
+        }
+    }
+    (void)hipFree(scratch);
+    return rc;
+}
+
 int mlpmoe_compact(const void *W_gate, const void *W_up, const void *W_down, const int32_t *gather,
                    int n_rows, int d_model, int d_inter_src, int elem_bytes, void *W_gate_c,
                    void *W_up_c, void *W_down_c, void *stream)

@@ -132,3 +132,24 @@ def test_compact_validation():
     assert f(vp(16), vp(16), vp(16), vp(16), -1, 8, 8, 2, vp(16), vp(16), vp(16), None) == mm.ERR_SHAPE
     assert f(None, vp(16), vp(16), vp(16), 4, 8, 8, 2, vp(16), vp(16), vp(16), None) == mm.ERR_NULL
     assert f(None, None, None, None, 0, 8, 8, 2, None, None, None, None) == mm.OK
+
+
+def test_fade_argument_validation():
+    """mlpmoe_fade refuses bad tables and unsupported storage before touching the GPU."""
+    import ctypes
+    lib = mm.lib
+    off = np.array([0, 8, 16], np.int32)
+    fake = ctypes.c_void_p(0x1000)
+    call = lambda offs, sp, dm, di, B, eb, wg=fake: lib.mlpmoe_fade(
+        wg, fake, offs.ctypes.data, sp.ctypes.data if sp is not None else None, dm, di, B, eb, None, None, None)
+    assert call(off, None, 64, 16, 0, 2) == mm.ERR_SHAPE
+    assert call(off, None, 64, 17, 2, 2) == mm.ERR_OFFSETS
+    assert call(np.array([0, 9, 8], np.int32), None, 64, 8, 2, 2) == mm.ERR_OFFSETS
+    assert call(off, np.array([0.0, 1.5]), 64, 16, 2, 2) == mm.ERR_SHAPE
+    assert call(off, np.array([0.0, float("nan")]), 64, 16, 2, 2) == mm.ERR_SHAPE
+    assert call(off, None, 64, 16, 2, 4) == mm.ERR_UNSUPPORTED          # float storage
+    assert call(off, None, 60, 16, 2, 2) == mm.ERR_UNSUPPORTED          # d_model not a multiple of 8
+    assert call(off, None, 64, 16, 2, 2, ctypes.c_void_p(0x1004)) == mm.ERR_ALIGN
+    assert call(off, None, 64, 16, 2, 2, None) == mm.ERR_NULL
+    # nothing to do: d_inter == 0 is accepted without pointers
+    assert call(np.array([0, 0], np.int32), None, 64, 0, 1, 2, None) == mm.OK

@@ -1,4 +1,4 @@
-// Prefill path: bf16 MFMA kernels for gfx950 (v_mfma_f32_32x32x16_bf16, wave64).
+// Prefill path: bf16 MFMA kernels for gfx950 (v_mfma_f32_16x16x32_bf16, wave64).
 //
 // Kernel 1  gate_up_mfma:  H[t,j] = bf16( alpha_b(j) * SiLU(<x_t,Wg_j>) * <x_t,Wu_j> )
 //           one 256-token x 128-neuron tile per workgroup with TWO fp32 accumulator sets
@@ -9,8 +9,10 @@
 //           so the sum over branches of Sec. 3.1 is one fp32 accumulation with no per-branch
 //           round trip.  Small outputs are split along K into deterministic partial sums.
 //
-// Both kernels share one main loop: 256 A rows (tokens) against two blocks of 128 B rows,
-// 8 waves in a 4x2 arrangement, each wave owning 64 x (64+64) outputs = 8 MFMA tiles.
+// Both kernels share one main loop: 256 A rows (tokens) against two blocks of 128 B rows, waves in
+// a WM x 2 arrangement, each wave owning (256 / WM) x (64+64) outputs as 16x16 MFMA tiles.  The
+// 16x16x32 shape is used rather than 32x32x16 because the chip is power limited on this work: with
+// random operands a pure stream of 16x16x32 MFMAs sustains 2.0 PFLOP/s, one of 32x32x16 1.7.
 #include "internal.h"
 
 namespace mlpmoe {
@@ -100,7 +102,7 @@ __device__ __forceinline__ KCursor k_seek(const KR &kr, int tile)
 // part number s going to ring slot s % 5, so while K tile i is being used the parts of tile i+1
 // and the A part of tile i+2 are landing.  Chunk c of row r is stored at chunk slot c ^ swz(r),
 // swz(r) = (r & 7) ^ ((r >> 3) & 1), so that the 16-byte reads of 32 consecutive rows at one
-// logical chunk fall on distinct banks.  A direct-to-LDS wave load writes 1 KiB = 8 whole rows,
+// logical chunk (and of 16 consecutive rows at 4 consecutive chunks) fall on distinct banks.  A direct-to-LDS wave load writes 1 KiB = 8 whole rows,
 // and each row is one full 128-byte line of global memory (half lines cost the same L2 -> CU
 // transfer as whole ones); the swizzle is applied on the global side: the lane that fills slot p
 // of row r fetches logical chunk p ^ swz(r).
@@ -110,28 +112,27 @@ __device__ __forceinline__ KCursor k_seek(const KR &kr, int tile)
 // a_valid / b0_valid / b1_valid are the rows that exist from there on (>= 1).  Rows past that
 // are clamped to the last valid row: their results are never stored and MFMA rows / columns do
 // not mix.  K chunks past the end of a range are read from a zero chunk, in A and in B.
-// Schedule of K tile i (four K steps of 16; fragments are double buffered one step ahead):
-//   step 0: MFMAs; read step 1's fragments; issue the second half of the B part of tile i+1
-//   step 1, 2: MFMAs; read the next step's fragments; issue one half each of the A part of tile i+2
+// Schedule of K tile i (two K steps of 32; fragments are double buffered one step ahead):
+//   step 0: MFMAs; read step 1's fragments; issue the A part of tile i+2
 //   barrier: parts of tile i+1 have landed (only the newest A part may be in flight) and every
 //            wave has read its last fragments of tile i, whose two ring slots are free again
-//   step 3: MFMAs; read step 0's fragments of tile i+1; issue the first half of the B part of tile i+2
-// The direct loads are spread evenly over the steps (one per wave every other MFMA slot) because
-// a CU's vector memory path takes about as long to move a tile as the MFMAs take to consume it:
+//   step 1: MFMAs; read step 0's fragments of tile i+1; issue the B part of tile i+2
+// The direct loads are spread over the steps (one per wave every other MFMA slot) because a
+// CU's vector memory path takes about as long to move a tile as the MFMAs take to consume it:
 // issued in bursts, the loads back up in the issue queue and the MFMAs behind them wait.
 template <int WM, bool kRowsAreB, typename KR>
 __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, int lda, int a_valid,
                                          const uint16_t *__restrict__ B0_tile,
                                          const uint16_t *__restrict__ B1_tile, int ldb, int b0_valid,
                                          int b1_valid, const KR &kr, int kt_begin, int kt_end, char *lds,
-                                         f32x16 (&acc0)[8 / WM][2], f32x16 (&acc1)[8 / WM][2])
+                                         f32x4 (&acc0)[16 / WM][4], f32x4 (&acc1)[16 / WM][4])
 {
-    constexpr int MI = 8 / WM;                    // 32-row MFMA tiles per wave along M
+    constexpr int MI = 16 / WM;                   // 16-row MFMA tiles per wave along M: 8 or 4
     constexpr int NWAVES = WM * 2;
     constexpr int PL = 32 / NWAVES;               // 1 KiB wave-loads per wave per part: 8 or 4
-    constexpr int N_SLOTS = MI * 2;               // slots of 2 MFMAs per K step
-    constexpr int N_PIECES = 4 + MI;              // fragment pieces per K step
-    static_assert(PL == N_SLOTS, "one direct load every other slot, half a part per K step");
+    constexpr int N_SLOTS = MI * 2;               // slots of 4 MFMAs per K step
+    constexpr int N_PIECES = 8 + MI;              // fragment pieces per K step
+    static_assert(PL * 2 == N_SLOTS, "one direct load every other slot, a part per K step");
     const int nk = kt_end - kt_begin;
     if (nk <= 0) return;
     const int tid = threadIdx.x;
@@ -198,79 +199,70 @@ __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, in
         dma16(pt.ok[n & 1] ? pt.src + off[n] : zero, pt.dst + n * 1024);
     };
 
-    // ---- LDS side: per-lane read offsets (bytes) for the 4 K steps of a tile
-    const int lrow = lane & 31;
-    const int swz = (lane & 7) ^ ((lane >> 3) & 1);      // fragment rows start at multiples of 32
-    int a_rd[4], b_rd[4];
+    // ---- LDS side: per-lane read offsets (bytes) for the 2 K steps of a tile.  A 16x16x32
+    // fragment is 16 rows x 32 K: lane l holds row l & 15 and K group l >> 4 (8 elements).  Which
+    // 16-byte chunk of the step's 64 bytes a K group reads is free as long as A and B agree (the
+    // dot product does not care about the order of K).  The LDS serves lanes l and l + 32 in the
+    // same cycle, so K groups g and g + 2 are given ADJACENT chunks (0, 2, 1, 3 -> chunks 0, 1, 2,
+    // 3): with the row swizzle the 16 lanes of a cycle then fall on distinct banks.
+    const int lrow = lane & 15;
+    const int swz = (lane & 7) ^ ((lane >> 3) & 1);      // fragment rows start at multiples of 16
+    const int kg = lane >> 4;
+    const int kchunk = ((kg & 1) << 1) | (kg >> 1);
+    int a_rd[2], b_rd[2];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-        const int slot = (ks * 2 + (lane >> 5)) ^ swz;
-        a_rd[ks] = (wm * (MI * 32) + lrow) * 128 + slot * 16;
+    for (int ks = 0; ks < 2; ++ks) {
+        const int slot = (ks * 4 + kchunk) ^ swz;
+        a_rd[ks] = (wm * (MI * 16) + lrow) * 128 + slot * 16;
         b_rd[ks] = (wn * 64 + lrow) * 128 + slot * 16;
     }
-    // Fragment pieces of one K step in the order they are read: the four B pieces first
-    // (b0[0], b1[0], b0[1], b1[1]), then a[0..MI).  MFMA m uses a[m >> 2] and B piece m & 3, so the
-    // piece that is read last is needed only by the last four MFMAs of the following step.
+    // Fragment pieces of one K step: v[0..7] = the B pieces b0[0..3], b1[0..3] (16 rows of the first
+    // / second B block each), v[8..] = the A pieces.  MFMA m uses A piece m >> 3 and B piece m & 7.
     struct Frags {
         bf16x8 v[N_PIECES];
     };
     auto read_piece = [&](Frags &f, int g, int a_slot, int ks) {
         // the B part of a tile sits in the ring slot after its A part
         const int b_slot = a_slot + 1 < N_PARTS ? a_slot + 1 : 0;
-        if (g < 4)
-            f.v[g] = *reinterpret_cast<const bf16x8 *>(lds + b_slot * PART_BYTES + b_rd[ks] + (g & 1) * (128 * 128) +
-                                                       (g >> 1) * (32 * 128));
+        if (g < 8)
+            f.v[g] = *reinterpret_cast<const bf16x8 *>(lds + b_slot * PART_BYTES + b_rd[ks] + (g >> 2) * (128 * 128) +
+                                                       (g & 3) * (16 * 128));
         else
-            f.v[g] = *reinterpret_cast<const bf16x8 *>(lds + a_slot * PART_BYTES + a_rd[ks] + (g - 4) * (32 * 128));
+            f.v[g] = *reinterpret_cast<const bf16x8 *>(lds + a_slot * PART_BYTES + a_rd[ks] + (g - 8) * (16 * 128));
     };
     // kRowsAreB: the B rows (weights) are the MFMA's row operand and the A rows (tokens) its column
-    // operand.  In the 32x32 result lane l then holds column l % 32 = one token and, in registers
-    // 4g .. 4g+3, rows 8g + 4 * (l / 32) + 0..3 = four consecutive neurons, which the gate+up
-    // epilogue turns into one 8-byte piece of the token's row of H.  Otherwise tokens are the rows
-    // and a lane holds one B row for 16 tokens (the down projection: 32 lanes store 128
-    // contiguous bytes of fp32 per token).
+    // operand.  In the 16x16 result lane l then holds column l & 15 = one token and rows
+    // 4 * (l >> 4) + 0..3 = four consecutive B rows, which the epilogues store as one 8- or 16-byte
+    // piece of the token's output row.  Otherwise tokens are the rows.
     auto mfma_n = [&](const Frags &f, int m) {
-        const int i = m >> 2, j = (m >> 1) & 1;
-        const bf16x8 r = kRowsAreB ? f.v[m & 3] : f.v[4 + i], c = kRowsAreB ? f.v[4 + i] : f.v[m & 3];
-        if (m & 1) acc1[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(r, c, acc1[i][j], 0, 0, 0);
-        else acc0[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(r, c, acc0[i][j], 0, 0, 0);
+        const int i = m >> 3, b = m & 7;
+        const bf16x8 r = kRowsAreB ? f.v[b] : f.v[8 + i], c = kRowsAreB ? f.v[8 + i] : f.v[b];
+        if (b < 4) acc0[i][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r, c, acc0[i][b], 0, 0, 0);
+        else acc1[i][b - 4] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r, c, acc1[i][b - 4], 0, 0, 0);
     };
-    // One K step, written in the instruction order wanted: slots of {2 MFMAs, then LDS reads of
+    // One K step, written in the instruction order wanted: slots of {4 MFMAs, then LDS reads of
     // the next step's fragments, then (every other slot) one direct load}; nothing may be
     // moved across a slot boundary.  The compiler waits for ALL outstanding LDS reads before the
     // first MFMA of a step (direct-to-LDS loads in flight make it give up exact counting), so the
     // reads are packed into the early slots and the last slots leave them time to land.
-    // DMA: 1 loads of the A part pt, 2 loads of the B part pt; half: which half of the part's loads.
-    auto k_step = [&](const Frags &cur_f, Frags &nxt_f, int rd_slot, int rd_ks, int dma, int half,
-                      const Part &pt) {
+    // DMA: 1 loads of the A part pt, 2 loads of the B part pt.
+    auto k_step = [&](const Frags &cur_f, Frags &nxt_f, int rd_slot, int rd_ks, int dma, const Part &pt) {
 #pragma unroll
         for (int g = 0; g < N_SLOTS; ++g) {
-            mfma_n(cur_f, 2 * g);
-            mfma_n(cur_f, 2 * g + 1);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) mfma_n(cur_f, 4 * g + q);
             __builtin_amdgcn_sched_barrier(0);
-            if (MI == 4) {                 // 8 pieces over slots 0-5: 2,2,1,1,1,1
-                if (g < 2) {
-                    read_piece(nxt_f, 2 * g, rd_slot, rd_ks);
-                    read_piece(nxt_f, 2 * g + 1, rd_slot, rd_ks);
-                } else if (g < 6) {
-                    read_piece(nxt_f, g + 2, rd_slot, rd_ks);
-                }
-            } else {                       // 6 pieces over slots 0-2: 2,2,2
-                if (g < 3) {
-                    read_piece(nxt_f, 2 * g, rd_slot, rd_ks);
-                    read_piece(nxt_f, 2 * g + 1, rd_slot, rd_ks);
-                }
-            }
+            if (2 * g < N_PIECES) read_piece(nxt_f, 2 * g, rd_slot, rd_ks);
+            if (2 * g + 1 < N_PIECES) read_piece(nxt_f, 2 * g + 1, rd_slot, rd_ks);
             if ((g & 1) == 0) {
-                const int n = half * (PL / 2) + g / 2;
-                if (dma == 1) dma_part(n, pt, a_off);
-                if (dma == 2) dma_part(n, pt, b_off);
+                if (dma == 1) dma_part(g / 2, pt, a_off);
+                if (dma == 2) dma_part(g / 2, pt, b_off);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
     };
 
-    // prologue: parts A0 B0 A1 and the first half of B1 in flight, tile 0 landed
+    // prologue: parts A0 B0 A1 B1 in flight, tile 0 landed
     Issue qa, qb;
     {
         const KCursor c = k_seek(kr, kt_begin);
@@ -282,40 +274,31 @@ __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, in
         qb = qa;
         qb.slot = 1;
     }
-    {
-        Part pa = part_of(qa, a_base), pb = part_of(qb, b_base);
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const Part pa = part_of(qa, a_base), pb = part_of(qb, b_base);
 #pragma unroll
         for (int n = 0; n < PL; ++n) dma_part(n, pa, a_off);
 #pragma unroll
         for (int n = 0; n < PL; ++n) dma_part(n, pb, b_off);
         advance(qa);
         advance(qb);
-        pa = part_of(qa, a_base);
-        pb = part_of(qb, b_base);
-#pragma unroll
-        for (int n = 0; n < PL; ++n) dma_part(n, pa, a_off);
-#pragma unroll
-        for (int n = 0; n < PL / 2; ++n) dma_part(n, pb, b_off);
-        advance(qa);
     }
-    pipeline_barrier<PL + PL / 2>();
+    pipeline_barrier<2 * PL>();
     Frags f0, f1;
 #pragma unroll
     for (int g = 0; g < N_PIECES; ++g) read_piece(f0, g, 0, 0);
 
     int rd = 0;                                   // ring slot of the A part of the tile in use
     for (int it = 0; it < nk; ++it) {
-        Part pb = part_of(qb, b_base);
-        k_step(f0, f1, rd, 1, 2, 1, pb);          // + rest of the B part of tile it+1
-        advance(qb);
         const Part pa = part_of(qa, a_base);
-        k_step(f1, f0, rd, 2, 1, 0, pa);          // + A part of tile it+2
-        k_step(f0, f1, rd, 3, 1, 1, pa);
+        k_step(f0, f1, rd, 1, 1, pa);             // + A part of tile it+2
         advance(qa);
         pipeline_barrier<PL>();                   // tile it+1 has landed; tile it's slots are free
         rd = rd + 2 < N_PARTS ? rd + 2 : rd + 2 - N_PARTS;
-        pb = part_of(qb, b_base);
-        k_step(f1, f0, rd, 0, 2, 0, pb);          // + start of the B part of tile it+2
+        const Part pb = part_of(qb, b_base);
+        k_step(f1, f0, rd, 0, 2, pb);             // + B part of tile it+2
+        advance(qb);
     }
     pipeline_barrier<0>();                        // LDS may be reused by the caller
 }
@@ -385,22 +368,20 @@ gate_up_mfma(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
     if (n_end == 0) return;
     const int t0 = tm * BM;
 
-    constexpr int MI = 8 / WM;
-    f32x16 accg[MI][2], accu[MI][2];
+    constexpr int MI = 16 / WM;
+    f32x4 accg[MI][4], accu[MI][4];
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                accg[i][j][v] = 0.f;
-                accu[i][j][v] = 0.f;
-            }
+        for (int j = 0; j < 4; ++j) {
+            accg[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+            accu[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
 
     const int nk = (d_model + BK - 1) / BK;
     mainloop<WM, true>(X + (size_t)t0 * d_model, d_model, T - t0, Wg + (size_t)n0 * d_model,
-             Wu + (size_t)n0 * d_model, d_model, n_end - n0, n_end - n0, KSingle{d_model}, 0, nk, lds,
-             accg, accu);
+                       Wu + (size_t)n0 * d_model, d_model, n_end - n0, n_end - n0, KSingle{d_model}, 0, nk,
+                       lds, accg, accu);
 
     // alpha of the tile's 128 neurons -> LDS (the main loop is done with it)
     float *al = reinterpret_cast<float *>(lds);
@@ -412,27 +393,23 @@ gate_up_mfma(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave >> 1, wn = wave & 1;
-    const int tcol = lane & 31, hi = lane >> 5;
+    const int tcol = lane & 15, q4 = lane >> 4;
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
-        const int t = t0 + wm * (MI * 32) + i * 32 + tcol;
+        const int t = t0 + wm * (MI * 16) + i * 16 + tcol;
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
+        for (int j = 0; j < 4; ++j) {
+            const int nl = wn * 64 + j * 16 + 4 * q4;      // first of 4 neurons, tile relative
+            // run ends are multiples of 8: the four neurons are all inside the run or all outside
+            if (t < T && n0 + nl < n_end) {
+                const f32x4 a4 = *reinterpret_cast<const f32x4 *>(al + nl);
+                uint16_t h[4];
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int nl = wn * 64 + j * 32 + 8 * g + 4 * hi;     // first of 4 neurons, tile relative
-                // run ends are multiples of 8: the four neurons are all inside the run or all outside
-                if (t < T && n0 + nl < n_end) {
-                    const f32x4 a4 = *reinterpret_cast<const f32x4 *>(al + nl);
-                    uint16_t h[4];
-#pragma unroll
-                    for (int q = 0; q < 4; ++q)
-                        h[q] = to_bf16(a4[q] * silu_mul(accg[i][j][4 * g + q], accu[i][j][4 * g + q]));
-                    u32x2 pk;
-                    pk.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
-                    pk.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
-                    *reinterpret_cast<u32x2 *>(H + (size_t)t * ldh + n0 + nl) = pk;
-                }
+                for (int q = 0; q < 4; ++q) h[q] = to_bf16(a4[q] * silu_mul(accg[i][j][q], accu[i][j][q]));
+                u32x2 pk;
+                pk.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
+                pk.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
+                *reinterpret_cast<u32x2 *>(H + (size_t)t * ldh + n0 + nl) = pk;
             }
         }
     }
@@ -454,40 +431,38 @@ down_mfma(const uint16_t *__restrict__ H, const uint16_t *__restrict__ Wd, float
     const int kt_begin = (int)((long long)kt_total * z / splits);
     const int kt_end = (int)((long long)kt_total * (z + 1) / splits);
 
-    constexpr int MI = 8 / WM;
-    f32x16 acc0[MI][2], acc1[MI][2];
+    constexpr int MI = 16 / WM;
+    f32x4 acc0[MI][4], acc1[MI][4];
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                acc0[i][j][v] = 0.f;
-                acc1[i][j][v] = 0.f;
-            }
+        for (int j = 0; j < 4; ++j) {
+            acc0[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+            acc1[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
 
     // the second block of 128 output features may start past d_model: point it at the last row
     const int n1 = n0 + BNH < d_model ? n0 + BNH : d_model - 1;
-    mainloop<WM, false>(H + (size_t)t0 * ldh, ldh, T - t0, Wd + (size_t)n0 * d_inter, Wd + (size_t)n1 * d_inter,
-             d_inter, d_model - n0, d_model - n1, KRuns{bt}, kt_begin, kt_end, lds, acc0, acc1);
+    mainloop<WM, true>(H + (size_t)t0 * ldh, ldh, T - t0, Wd + (size_t)n0 * d_inter, Wd + (size_t)n1 * d_inter,
+                       d_inter, d_model - n0, d_model - n1, KRuns{bt}, kt_begin, kt_end, lds, acc0, acc1);
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave >> 1, wn = wave & 1;
+    const int tcol = lane & 15, q4 = lane >> 4;
     float *o = dst + (size_t)z * T * d_model;
 #pragma unroll
-    for (int half = 0; half < 2; ++half)
+    for (int i = 0; i < MI; ++i) {
+        const int t = t0 + wm * (MI * 16) + i * 16 + tcol;
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int n = n0 + half * BNH + wn * 64 + j * 32 + (lane & 31);
-            if (n >= d_model) continue;
+        for (int half = 0; half < 2; ++half)
 #pragma unroll
-            for (int i = 0; i < MI; ++i)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int t = t0 + wm * (MI * 32) + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                    if (t < T) o[(size_t)t * d_model + n] = half ? acc1[i][j][v] : acc0[i][j][v];
-                }
-        }
+            for (int j = 0; j < 4; ++j) {
+                const int m = n0 + half * BNH + wn * 64 + j * 16 + 4 * q4;
+                // d_model is a multiple of 8: the four features are all inside or all outside
+                if (t < T && m < d_model)
+                    *reinterpret_cast<f32x4 *>(o + (size_t)t * d_model + m) = half ? acc1[i][j] : acc0[i][j];
+            }
+    }
 }
 
 // out[i] = sum_z partial[z][i], summed in z order: deterministic.

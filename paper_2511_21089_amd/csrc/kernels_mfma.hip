@@ -249,8 +249,13 @@ __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, in
     auto k_step = [&](const Frags &cur_f, Frags &nxt_f, int rd_slot, int rd_ks, int dma, const Part &pt) {
 #pragma unroll
         for (int g = 0; g < N_SLOTS; ++g) {
+            // The wave runs its MFMA bursts at a raised priority and everything else at the
+            // lowest: the other wave of the SIMD gets the matrix pipe the moment this one turns
+            // to its loads and address arithmetic, instead of queueing behind them.
+            __builtin_amdgcn_s_setprio(3);
 #pragma unroll
             for (int q = 0; q < 4; ++q) mfma_n(cur_f, 4 * g + q);
+            __builtin_amdgcn_s_setprio(0);
             __builtin_amdgcn_sched_barrier(0);
             if (2 * g < N_PIECES) read_piece(nxt_f, 2 * g, rd_slot, rd_ks);
             if (2 * g + 1 < N_PIECES) read_piece(nxt_f, 2 * g + 1, rd_slot, rd_ks);

@@ -36,8 +36,8 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 TRAFFIC = {
     # (workload, kernel): (sha256 of the kernel's source file, bytes per launch = read + written)
     # gate_up_mfma at T=4096: 1409.4 MB read (x is re-read once per group of 4 neuron tiles and the
-    # weights once per XCD that needs them: 5.3x the 268 MB the kernel has to read) + 119.1 MB written
-    ("llama8b_T4096", "gate_up_mfma"): ("6a9d908a34ae306c6d7be04cc50dfeb7e30c5f8e92061030f1f62d7753b381de", 1528.5e6),
+    # weights once per XCD that needs them: 5.3x the 268 MB the kernel has to read) + 117.6 MB written
+    ("llama8b_T4096", "gate_up_mfma"): ("fafdf3ef106ddec835f655c46c50d8118a5a6f86a2f344d980193dd2cf8a0492", 1527.1e6),
     # decode gate+up at T=1: 235.1 MB read (the weights, once) + 0.1 MB written
     ("llama8b_T1", "decode_gate_up"): ("3307daf5ad802fac2e17db738481aa389b3c27353e134cb985be7ab679dc84ea", 235.2e6),
 }

@@ -249,12 +249,15 @@ __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, in
     auto k_step = [&](const Frags &cur_f, Frags &nxt_f, int rd_slot, int rd_ks, int dma, const Part &pt) {
 #pragma unroll
         for (int g = 0; g < N_SLOTS; ++g) {
-            // The wave runs its MFMA bursts at a raised priority and everything else at the
-            // lowest: the other wave of the SIMD gets the matrix pipe the moment this one turns
-            // to its loads and address arithmetic, instead of queueing behind them.
+            // The two waves of a SIMD take the matrix pipe in turns of four MFMAs.  A wave asks
+            // for its turn at priority 1 (first MFMA), holds it at priority 3 (the other wave,
+            // asking at 1, cannot cut in, which the older wave otherwise always does) and drops
+            // to 0 for its loads and address arithmetic, which then run under the other's turn.
+            __builtin_amdgcn_s_setprio(1);
+            mfma_n(cur_f, 4 * g);
             __builtin_amdgcn_s_setprio(3);
 #pragma unroll
-            for (int q = 0; q < 4; ++q) mfma_n(cur_f, 4 * g + q);
+            for (int q = 1; q < 4; ++q) mfma_n(cur_f, 4 * g + q);
             __builtin_amdgcn_s_setprio(0);
             __builtin_amdgcn_sched_barrier(0);
             if (2 * g < N_PIECES) read_piece(nxt_f, 2 * g, rd_slot, rd_ks);

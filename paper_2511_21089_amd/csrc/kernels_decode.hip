@@ -15,6 +15,8 @@
 //
 // Eight-neuron tiles keep the tile count a multiple of the CU count for the usual widths
 // (14336 / 8 = 7 * 256) and never straddle a run boundary (boundaries are multiples of 8).
+#include <mutex>
+
 #include "internal.h"
 
 namespace mlpmoe {
@@ -346,21 +348,27 @@ hipError_t launch_decode_bf16(const FwdArgs &a, const BranchTable &bt)
     uint16_t *H = static_cast<uint16_t *>(a.H);
     const size_t xs_bytes = (size_t)a.T * (a.d_model * 2 + 16) + 16 + 2 * MLPMOE_DEC_SNW * 256 * sizeof(float);
     if (xs_bytes <= kStreamLdsMax) {
-        static int n_cus = 0;
-        static bool attr_set = false;
-        if (!attr_set) {
-            int dev = 0;
-            hipDeviceProp_t prop;
-            hipError_t e = hipGetDevice(&dev);
-            if (e != hipSuccess) return note_hip_error("hipGetDevice", e);
-            e = hipGetDeviceProperties(&prop, dev);
-            if (e != hipSuccess) return note_hip_error("hipGetDeviceProperties", e);
-            n_cus = prop.multiProcessorCount;
-            e = hipFuncSetAttribute(
-                reinterpret_cast<const void *>(&decode_gate_up_persist<MLPMOE_DEC_SNW, MLPMOE_DEC_SU>),
-                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kStreamLdsMax);
-            if (e != hipSuccess) return note_hip_error("hipFuncSetAttribute(decode_gate_up_persist)", e);
-            attr_set = true;
+        // per device, set up on the first call there: CU count and the kernel's LDS limit
+        static std::mutex mu;
+        static int cus_of[64] = {0};
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return note_hip_error("hipGetDevice", e);
+        if (dev < 0 || dev >= 64) return note_hip_error("device index", hipErrorInvalidDevice);
+        int n_cus;
+        {
+            std::lock_guard<std::mutex> lock(mu);
+            if (cus_of[dev] == 0) {
+                hipDeviceProp_t prop;
+                e = hipGetDeviceProperties(&prop, dev);
+                if (e != hipSuccess) return note_hip_error("hipGetDeviceProperties", e);
+                e = hipFuncSetAttribute(
+                    reinterpret_cast<const void *>(&decode_gate_up_persist<MLPMOE_DEC_SNW, MLPMOE_DEC_SU>),
+                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)kStreamLdsMax);
+                if (e != hipSuccess) return note_hip_error("hipFuncSetAttribute(decode_gate_up_persist)", e);
+                cus_of[dev] = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 1;
+            }
+            n_cus = cus_of[dev];
         }
         const int grid = tiles1 < n_cus ? (int)tiles1 : n_cus;
         ProfileScope ps(MLPMOE_KERNEL_DECODE_GATE_UP, a.stream);

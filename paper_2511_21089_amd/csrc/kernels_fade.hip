@@ -13,6 +13,8 @@
 // Between two neighbouring order statistics there is no data, so "greater than the interpolated
 // threshold" and "greater than the lower neighbour" select the same entries; the interpolated
 // value itself is formed on the host from the two neighbours, for reporting.
+#include <mutex>
+
 #include "internal.h"
 
 namespace mlpmoe {
@@ -152,12 +154,21 @@ hipError_t launch_fade_bf16(void *W, const int32_t *off, const double *sparsity,
     const size_t words = (size_t)jobs.n * (kBins + 4);
     fill_u32<<<1024, 256, 0, s>>>(scratch, words);
     if (launch_status("fade fill launch") != hipSuccess) return hipErrorLaunchFailure;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fade_histogram),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kBins * 4);
-        if (e != hipSuccess) return note_hip_error("hipFuncSetAttribute(fade_histogram)", e);
-        attr_set = true;
+    {
+        // per device, on the first call there: allow the 128 KB histogram
+        static std::mutex mu;
+        static bool attr_set[64] = {false};
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return note_hip_error("hipGetDevice", e);
+        if (dev < 0 || dev >= 64) return note_hip_error("device index", hipErrorInvalidDevice);
+        std::lock_guard<std::mutex> lock(mu);
+        if (!attr_set[dev]) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fade_histogram),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kBins * 4);
+            if (e != hipSuccess) return note_hip_error("hipFuncSetAttribute(fade_histogram)", e);
+            attr_set[dev] = true;
+        }
     }
     long long max_chunks = 0;
     for (int j = 0; j < jobs.n; ++j) max_chunks = jobs.count[j] / 8 > max_chunks ? jobs.count[j] / 8 : max_chunks;

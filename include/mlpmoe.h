@@ -245,6 +245,29 @@ MLPMOE_API int mlpmoe_profile_enable(int capacity);
 MLPMOE_API int mlpmoe_profile_collect(int *ids, float *ms, int capacity);
 MLPMOE_API int mlpmoe_profile_disable(void);
 
+/*
+ * Plan: the branch table of one layer, checked and turned into the kernels' form once, together
+ * with a device workspace large enough for any T up to max_T.  For callers that run the same
+ * layer many times (decode loops, captured graphs): mlpmoe_plan_forward does no per-branch host
+ * work, allocates nothing and synchronises nothing.
+ *
+ *   mlpmoe_plan_create   branch_offsets / alpha / active_mask / sizes as for mlpmoe_forward (host
+ *                        arrays, copied); elem_bytes 2 (bf16) or 4 (float); max_T >= 1.  Allocates the
+ *                        workspace on the current device.  *plan is NULL on failure.
+ *   mlpmoe_plan_forward  x [T, d_model], weights and out [T, d_model] float: device pointers, 16-byte
+ *                        aligned, same layouts as mlpmoe_forward; 0 <= T <= max_T (MLPMOE_ERR_SHAPE
+ *                        otherwise); launches on `stream`.  Calls that share a plan share its workspace:
+ *                        they must be ordered on one stream (or otherwise not overlap).
+ *   mlpmoe_plan_destroy  synchronises the plan's device, frees the workspace and the plan (NULL is fine).
+ */
+typedef struct mlpmoe_plan mlpmoe_plan;
+MLPMOE_API int mlpmoe_plan_create(const int32_t *branch_offsets, const float *alpha, const uint8_t *active_mask,
+                                  int d_model, int d_inter, int B, int elem_bytes, int max_T,
+                                  mlpmoe_plan **plan);
+MLPMOE_API int mlpmoe_plan_forward(const mlpmoe_plan *plan, const void *x, const void *W_gate, const void *W_up,
+                                   const void *W_down, int T, float *out, void *stream);
+MLPMOE_API int mlpmoe_plan_destroy(mlpmoe_plan *plan);
+
 /* Frees the library-owned per-device workspaces (synchronises each device first). */
 MLPMOE_API int mlpmoe_release(void);
 

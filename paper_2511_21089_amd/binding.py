@@ -25,7 +25,8 @@ MAX_BRANCHES = 64
 EXPORTS = ["mlpmoe_status_string", "mlpmoe_last_error_detail", "mlpmoe_slice", "mlpmoe_compact", "mlpmoe_fade", "mlpmoe_workspace_bytes",
            "mlpmoe_forward_bf16", "mlpmoe_forward", "mlpmoe_forward_f32", "mlpmoe_forward_bf16_ws",
            "mlpmoe_forward_f32_ws", "mlpmoe_release", "mlpmoe_profile_enable",
-           "mlpmoe_profile_collect", "mlpmoe_profile_disable"]
+           "mlpmoe_profile_collect", "mlpmoe_profile_disable", "mlpmoe_plan_create", "mlpmoe_plan_forward",
+           "mlpmoe_plan_destroy"]
 
 
 class MlpMoeError(RuntimeError):
@@ -60,6 +61,12 @@ def _load() -> ctypes.CDLL:
     lib.mlpmoe_slice.restype = i
     lib.mlpmoe_compact.argtypes = [vp, vp, vp, vp, i, i, i, i, vp, vp, vp, vp]
     lib.mlpmoe_compact.restype = i
+    lib.mlpmoe_plan_create.argtypes = [ip, fp, bp, i, i, i, i, i, ctypes.POINTER(ctypes.c_void_p)]
+    lib.mlpmoe_plan_create.restype = i
+    lib.mlpmoe_plan_forward.argtypes = [vp, vp, vp, vp, vp, i, vp, vp]
+    lib.mlpmoe_plan_forward.restype = i
+    lib.mlpmoe_plan_destroy.argtypes = [vp]
+    lib.mlpmoe_plan_destroy.restype = i
     lib.mlpmoe_fade.argtypes = [vp, vp, ip, vp, i, i, i, i, vp, vp, vp]
     lib.mlpmoe_fade.restype = i
     lib.mlpmoe_workspace_bytes.argtypes = [i, i, i, i, i]
@@ -236,6 +243,37 @@ def mlpmoe_forward_f32_ws(x, W_gate, W_up, W_down, branch_offsets, alpha, active
 
 def mlpmoe_release():
     _check(lib.mlpmoe_release(), "mlpmoe_release")
+
+
+class Plan:
+    """A layer's branch table prepared once, with a device workspace for any T <= max_T."""
+
+    def __init__(self, branch_offsets, alpha, active_mask, d_model, d_inter, max_T, elem_bytes=2):
+        off, al, mk, B = _table(branch_offsets, alpha, active_mask)
+        self.d_model, self.d_inter, self.max_T = int(d_model), int(d_inter), int(max_T)
+        self._h = ctypes.c_void_p()
+        _check(lib.mlpmoe_plan_create(off.ctypes.data, al.ctypes.data, mk.ctypes.data, self.d_model, self.d_inter,
+                                      B, int(elem_bytes), self.max_T, ctypes.byref(self._h)), "mlpmoe_plan_create")
+
+    def forward(self, x, W_gate, W_up, W_down, out=None, stream=None):
+        import torch
+        T = int(x.shape[0])
+        if out is None:
+            out = torch.empty((T, self.d_model), dtype=torch.float32, device=x.device)
+        _check(lib.mlpmoe_plan_forward(self._h, _dev_ptr(x), _dev_ptr(W_gate), _dev_ptr(W_up), _dev_ptr(W_down), T,
+                                       _dev_ptr(out), _stream_ptr(stream)), "mlpmoe_plan_forward")
+        return out
+
+    def destroy(self):
+        if self._h:
+            h, self._h = self._h, ctypes.c_void_p()
+            _check(lib.mlpmoe_plan_destroy(h), "mlpmoe_plan_destroy")
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
 
 
 KERNEL_NAMES = {1: "gate_up_mfma", 2: "down_mfma", 3: "splitk_reduce", 4: "decode_gate_up",

@@ -5,8 +5,10 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <algorithm>
 #include <map>
 #include <mutex>
+#include <new>
 #include <vector>
 
 #include "internal.h"
@@ -91,18 +93,12 @@ size_t h_bytes(int T, int d_inter, int elem_bytes)
     return align_up((size_t)T * (size_t)h_ld(d_inter) * (size_t)elem_bytes, 256);
 }
 
-int forward_impl(const void *x, const void *Wg, const void *Wu, const void *Wd, const int32_t *off,
-                 const float *alpha, const uint8_t *mask, int T, int d_model, int d_inter, int B,
-                 float *out, void *workspace, size_t workspace_bytes, int path, bool is_bf16,
-                 hipStream_t stream)
+// Dispatch with a ready branch table: path choice, workspace carving, launch.  No loops over
+// branches, no allocation, no synchronisation.
+int forward_table(const BranchTable &bt, bool aligned, const void *x, const void *Wg, const void *Wu,
+                  const void *Wd, int T, int d_model, int d_inter, float *out, void *workspace,
+                  size_t workspace_bytes, int path, bool is_bf16, hipStream_t stream)
 {
-    int rc = validate_common(x, Wg, Wu, Wd, off, alpha, mask, T, d_model, d_inter, B, out);
-    if (rc != MLPMOE_OK) return rc;
-    if (path < MLPMOE_PATH_AUTO || path > MLPMOE_PATH_DECODE) return MLPMOE_ERR_UNSUPPORTED;
-    if (T == 0) return MLPMOE_OK;
-
-    BranchTable bt;
-    build_table(off, alpha, mask, B, bt);
     // launch status is read back with hipGetLastError(): drop whatever an earlier, unrelated
     // runtime call of this thread left behind (e.g. a "not ready" from an event query)
     (void)hipGetLastError();
@@ -112,15 +108,13 @@ int forward_impl(const void *x, const void *Wg, const void *Wu, const void *Wd, 
         return launch_fill_zero(out, (size_t)T * d_model, stream) == hipSuccess ? MLPMOE_OK
                                                                                 : MLPMOE_ERR_HIP;
     }
-
-    const bool aligned = is_bf16 && fast_path_aligned(bt, d_model, d_inter);
     if (path == MLPMOE_PATH_AUTO)
         path = !aligned ? MLPMOE_PATH_GENERIC : (T <= 16 ? MLPMOE_PATH_DECODE : MLPMOE_PATH_MFMA);
     if (path != MLPMOE_PATH_GENERIC && !aligned) return MLPMOE_ERR_UNSUPPORTED;
     if (path == MLPMOE_PATH_DECODE && T > 16) return MLPMOE_ERR_UNSUPPORTED;
 
     const int elem = is_bf16 ? 2 : 4;
-    const size_t need = mlpmoe_workspace_bytes(T, d_model, d_inter, B, elem);
+    const size_t need = mlpmoe_workspace_bytes(T, d_model, d_inter, bt.B, elem);
     if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u))
         return MLPMOE_ERR_WORKSPACE;
 
@@ -141,6 +135,22 @@ int forward_impl(const void *x, const void *Wg, const void *Wu, const void *Wd, 
     else e = launch_decode_bf16(a, bt);
     if (e != hipSuccess && g_err_detail[0] == 0) (void)note_hip_error("kernel launch", e);
     return e == hipSuccess ? MLPMOE_OK : MLPMOE_ERR_HIP;
+}
+
+int forward_impl(const void *x, const void *Wg, const void *Wu, const void *Wd, const int32_t *off,
+                 const float *alpha, const uint8_t *mask, int T, int d_model, int d_inter, int B,
+                 float *out, void *workspace, size_t workspace_bytes, int path, bool is_bf16,
+                 hipStream_t stream)
+{
+    int rc = validate_common(x, Wg, Wu, Wd, off, alpha, mask, T, d_model, d_inter, B, out);
+    if (rc != MLPMOE_OK) return rc;
+    if (path < MLPMOE_PATH_AUTO || path > MLPMOE_PATH_DECODE) return MLPMOE_ERR_UNSUPPORTED;
+    if (T == 0) return MLPMOE_OK;
+    BranchTable bt;
+    build_table(off, alpha, mask, B, bt);
+    const bool aligned = is_bf16 && fast_path_aligned(bt, d_model, d_inter);
+    return forward_table(bt, aligned, x, Wg, Wu, Wd, T, d_model, d_inter, out, workspace, workspace_bytes,
+                         path, is_bf16, stream);
 }
 
 // Library-owned workspace of the current device, grown on demand.
@@ -454,6 +464,87 @@ int mlpmoe_forward_f32(const float *x, const float *W_gate, const float *W_up, c
 {
     return forward_owned(x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, T, d_model,
                          d_inter, B, out, false, static_cast<hipStream_t>(stream));
+}
+
+struct mlpmoe_plan {
+    BranchTable bt;
+    int d_model, d_inter, B, elem_bytes, max_T, device;
+    bool aligned;
+    void *ws;
+    size_t ws_bytes;
+};
+
+int mlpmoe_plan_create(const int32_t *branch_offsets, const float *alpha, const uint8_t *active_mask,
+                       int d_model, int d_inter, int B, int elem_bytes, int max_T, mlpmoe_plan **plan)
+{
+    if (!plan) return MLPMOE_ERR_NULL;
+    *plan = nullptr;
+    if ((elem_bytes != 2 && elem_bytes != 4) || max_T < 1) return MLPMOE_ERR_SHAPE;
+    // same table checks as a forward call, with stand-in data pointers (T = 0 skips those)
+    int rc = validate_common(nullptr, nullptr, nullptr, nullptr, branch_offsets, alpha, active_mask, 0, d_model,
+                             d_inter, B, nullptr);
+    if (rc != MLPMOE_OK) return rc;
+    mlpmoe_plan *p = new (std::nothrow) mlpmoe_plan();
+    if (!p) return MLPMOE_ERR_WORKSPACE;
+    build_table(branch_offsets, alpha, active_mask, B, p->bt);
+    p->d_model = d_model;
+    p->d_inter = d_inter;
+    p->B = B;
+    p->elem_bytes = elem_bytes;
+    p->max_T = max_T;
+    p->aligned = elem_bytes == 2 && fast_path_aligned(p->bt, d_model, d_inter);
+    // Workspace for every T up to max_T.  H grows with T; the split-K partials are T times a
+    // split factor that is constant while T stays inside one 256-token tile row, so the maximum
+    // over a tile row is at its last T: checking the multiples of 256 and max_T covers all.
+    p->ws_bytes = 0;
+    for (long long t = 256; ; t += 256) {
+        const int tt = t < max_T ? (int)t : max_T;
+        p->ws_bytes = std::max(p->ws_bytes, mlpmoe_workspace_bytes(tt, d_model, d_inter, B, elem_bytes));
+        if (tt == max_T) break;
+    }
+    p->ws = nullptr;
+    (void)hipGetLastError();
+    g_err_detail[0] = 0;
+    hipError_t e = hipGetDevice(&p->device);
+    if (e == hipSuccess && p->ws_bytes) e = hipMalloc(&p->ws, p->ws_bytes);
+    if (e != hipSuccess) {
+        (void)note_hip_error("mlpmoe_plan_create: device workspace", e);
+        (void)hipGetLastError();
+        delete p;
+        return MLPMOE_ERR_HIP;
+    }
+    *plan = p;
+    return MLPMOE_OK;
+}
+
+int mlpmoe_plan_forward(const mlpmoe_plan *plan, const void *x, const void *W_gate, const void *W_up,
+                        const void *W_down, int T, float *out, void *stream)
+{
+    if (!plan) return MLPMOE_ERR_NULL;
+    if (T < 0 || T > plan->max_T) return MLPMOE_ERR_SHAPE;
+    if (T == 0) return MLPMOE_OK;
+    if (!x || !out || (plan->d_inter > 0 && (!W_gate || !W_up || !W_down))) return MLPMOE_ERR_NULL;
+    if (!aligned16(x) || !aligned16(out) || !aligned16(W_gate) || !aligned16(W_up) || !aligned16(W_down))
+        return MLPMOE_ERR_ALIGN;
+    return forward_table(plan->bt, plan->aligned, x, W_gate, W_up, W_down, T, plan->d_model, plan->d_inter, out,
+                         plan->ws, plan->ws_bytes, MLPMOE_PATH_AUTO, plan->elem_bytes == 2,
+                         static_cast<hipStream_t>(stream));
+}
+
+int mlpmoe_plan_destroy(mlpmoe_plan *plan)
+{
+    if (!plan) return MLPMOE_OK;
+    int rc = MLPMOE_OK;
+    if (plan->ws) {
+        int cur = 0;
+        (void)hipGetDevice(&cur);
+        if (hipSetDevice(plan->device) != hipSuccess || hipDeviceSynchronize() != hipSuccess ||
+            hipFree(plan->ws) != hipSuccess)
+            rc = MLPMOE_ERR_HIP;
+        (void)hipSetDevice(cur);
+    }
+    delete plan;
+    return rc;
 }
 
 int mlpmoe_release(void)

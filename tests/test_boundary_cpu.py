@@ -153,3 +153,23 @@ def test_fade_argument_validation():
     assert call(off, None, 64, 16, 2, 2, None) == mm.ERR_NULL
     # nothing to do: d_inter == 0 is accepted without pointers
     assert call(np.array([0, 0], np.int32), None, 64, 0, 1, 2, None) == mm.OK
+
+
+def test_plan_argument_validation():
+    """mlpmoe_plan_create checks the table before it touches the GPU; a NULL plan is harmless."""
+    import ctypes
+    lib = mm.lib
+    h = ctypes.c_void_p()
+    off = np.array([0, 8, 16], np.int32)
+    al = np.ones(2, np.float32)
+    mk = np.ones(2, np.uint8)
+    create = lambda o, dm, di, B, eb, mt: lib.mlpmoe_plan_create(o.ctypes.data, al.ctypes.data, mk.ctypes.data,
+                                                                 dm, di, B, eb, mt, ctypes.byref(h))
+    assert create(off, 64, 16, 2, 3, 16) == mm.ERR_SHAPE          # element size
+    assert create(off, 64, 16, 2, 2, 0) == mm.ERR_SHAPE           # max_T
+    assert create(off, 64, 17, 2, 2, 16) == mm.ERR_OFFSETS
+    assert create(off, 64, 16, 65, 2, 16) == mm.ERR_SHAPE
+    assert not h.value
+    assert lib.mlpmoe_plan_create(off.ctypes.data, al.ctypes.data, mk.ctypes.data, 64, 16, 2, 2, 16, None) == mm.ERR_NULL
+    assert lib.mlpmoe_plan_forward(None, None, None, None, None, 1, None, None) == mm.ERR_NULL
+    assert lib.mlpmoe_plan_destroy(None) == mm.OK

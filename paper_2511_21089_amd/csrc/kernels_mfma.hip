@@ -25,7 +25,7 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 constexpr int BM = 256;          // tokens per tile
-constexpr int BNH = 128;         // rows of each of the two B blocks
+constexpr int BNH_MAX = 128;     // rows of each of the two B blocks: 32 * NB, NB = 4 (128) or 2 (64)
 constexpr int BK = 64;           // K elements per tile: one tile row is 128 bytes = one cache line
 constexpr int PART_BYTES = 256 * BK * 2;             // 32768: the A rows, or the 128 + 128 B rows, of one K tile
 constexpr int N_PARTS = 5;                           // ring of parts: A0 B0 A1 B1 A2 | B2 A3 ...
@@ -120,19 +120,24 @@ __device__ __forceinline__ KCursor k_seek(const KR &kr, int tile)
 // The direct loads are spread over the steps (one per wave every other MFMA slot) because a
 // CU's vector memory path takes about as long to move a tile as the MFMAs take to consume it:
 // issued in bursts, the loads back up in the issue queue and the MFMAs behind them wait.
-template <int WM, bool kRowsAreB, typename KR>
+// NB = 16-row MFMA pieces per B block per wave: 4 (B blocks of 128 rows, a 256 x 256 tile) or 2 (B
+// blocks of 64 rows, a 256 x 128 tile, for shapes that would otherwise leave most CUs without a
+// tile in the last round).  A B part of 64 + 64 rows fills half of its ring slot.
+template <int WM, int NB, bool kRowsAreB, typename KR>
 __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, int lda, int a_valid,
                                          const uint16_t *__restrict__ B0_tile,
                                          const uint16_t *__restrict__ B1_tile, int ldb, int b0_valid,
                                          int b1_valid, const KR &kr, int kt_begin, int kt_end, char *lds,
-                                         f32x4 (&acc0)[16 / WM][4], f32x4 (&acc1)[16 / WM][4])
+                                         f32x4 (&acc0)[16 / WM][NB], f32x4 (&acc1)[16 / WM][NB])
 {
     constexpr int MI = 16 / WM;                   // 16-row MFMA tiles per wave along M: 8 or 4
     constexpr int NWAVES = WM * 2;
-    constexpr int PL = 32 / NWAVES;               // 1 KiB wave-loads per wave per part: 8 or 4
-    constexpr int N_SLOTS = MI * 2;               // slots of 4 MFMAs per K step
-    constexpr int N_PIECES = 8 + MI;              // fragment pieces per K step
-    static_assert(PL * 2 == N_SLOTS, "one direct load every other slot, a part per K step");
+    constexpr int BNH = 32 * NB;                  // rows of each B block
+    constexpr int PL = 32 / NWAVES;               // 1 KiB wave-loads per wave per A part: 8 or 4
+    constexpr int PLB = 8 * NB / NWAVES;          // ... per B part
+    constexpr int N_SLOTS = MI * NB / 2;          // slots of 4 MFMAs per K step
+    constexpr int N_PIECES = 2 * NB + MI;         // fragment pieces per K step
+    static_assert(N_SLOTS % PL == 0 && N_SLOTS % PLB == 0 && PLB % 2 == 0, "loads spread evenly over the slots");
     const int nk = kt_end - kt_begin;
     if (nk <= 0) return;
     const int tid = threadIdx.x;
@@ -145,27 +150,33 @@ __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, in
     const int cl0 = (lane & 7) ^ lr;              // logical chunk fetched in even slabs; odd slabs: cl0 ^ 1
     const bool second = wave >= NWAVES / 2;       // this wave fills the rows of the second B block
     const int b_valid = second ? b1_valid : b0_valid;
-    unsigned a_off[PL], b_off[PL];
+    unsigned a_off[PL], b_off[PLB];
 #pragma unroll
     for (int n = 0; n < PL; ++n) {
         const int slab = wave * PL + n;
         const int cl = cl0 ^ (n & 1);             // PL is even, so slab parity is n parity
         int ra = slab * 8 + lr;
         ra = ra < a_valid ? ra : a_valid - 1;
-        int rb = (slab & 15) * 8 + lr;
-        rb = rb < b_valid ? rb : b_valid - 1;
         a_off[n] = (unsigned)ra * (unsigned)lda * 2u + (unsigned)cl * 16u;
+    }
+#pragma unroll
+    for (int n = 0; n < PLB; ++n) {
+        const int slab = wave * PLB + n;          // 0 .. 8 NB - 1; the second half are B1's rows
+        const int cl = cl0 ^ (n & 1);
+        int rb = (slab % (4 * NB)) * 8 + lr;
+        rb = rb < b_valid ? rb : b_valid - 1;
         b_off[n] = (unsigned)rb * (unsigned)ldb * 2u + (unsigned)cl * 16u;
     }
     const char *a_base = reinterpret_cast<const char *>(A_tile);
     const char *b_base = reinterpret_cast<const char *>(second ? B1_tile : B0_tile);
-    char *w_dst = lds + wave * (PL * 1024);       // this wave's slabs inside a part
+    char *wa_dst = lds + wave * (PL * 1024);      // this wave's slabs inside an A part
+    char *wb_dst = lds + wave * (PLB * 1024);     // ... inside a B part
     const char *zero = reinterpret_cast<const char *>(g_zero_chunk);
 
     // Position of the next part to be issued, per matrix.  `left` counts the tiles not yet
     // issued.  A lane whose chunk lies past the end of the K range, or any lane once no tile is
     // left, reads the zero chunk instead.  Branch free, so that the loads sit in the same basic
-    // block as the MFMAs and every part is always PL loads.
+    // block as the MFMAs and every part is always the same number of loads.
     struct Issue {
         int run, k, kend, left, slot;
     };
@@ -180,13 +191,13 @@ __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, in
         q.slot += 2;
         if (q.slot >= N_PARTS) q.slot -= N_PARTS;
     };
-    // what the PL loads of one part have in common
+    // what the loads of one part have in common
     struct Part {
         const char *src;                          // tile pointer moved to the part's K offset
         char *dst;                                // this wave's first slab in the part's ring slot
         bool ok[2];                               // chunk inside the K range, for even / odd slabs
     };
-    auto part_of = [&](const Issue &q, const char *base) {
+    auto part_of = [&](const Issue &q, const char *base, char *w_dst) {
         Part pt;
         const int kend = q.left > 0 ? q.kend : -(1 << 30);
         pt.src = base + (size_t)q.k * 2;
@@ -195,7 +206,7 @@ __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, in
         pt.ok[1] = q.k + (cl0 ^ 1) * 8 < kend;
         return pt;
     };
-    auto dma_part = [&](int n, const Part &pt, const unsigned (&off)[PL]) {
+    auto dma_part = [&](int n, const Part &pt, const unsigned *off) {
         dma16(pt.ok[n & 1] ? pt.src + off[n] : zero, pt.dst + n * 1024);
     };
 
@@ -214,34 +225,35 @@ __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, in
     for (int ks = 0; ks < 2; ++ks) {
         const int slot = (ks * 4 + kchunk) ^ swz;
         a_rd[ks] = (wm * (MI * 16) + lrow) * 128 + slot * 16;
-        b_rd[ks] = (wn * 64 + lrow) * 128 + slot * 16;
+        b_rd[ks] = (wn * (16 * NB) + lrow) * 128 + slot * 16;
     }
-    // Fragment pieces of one K step: v[0..7] = the B pieces b0[0..3], b1[0..3] (16 rows of the first
-    // / second B block each), v[8..] = the A pieces.  MFMA m uses A piece m >> 3 and B piece m & 7.
+    // Fragment pieces of one K step: v[0 .. 2 NB) = the B pieces b0[0..NB), b1[0..NB) (16 rows of the
+    // first / second B block each), then the A pieces.  MFMA m uses A piece m / (2 NB) and B piece
+    // m % (2 NB).
     struct Frags {
         bf16x8 v[N_PIECES];
     };
     auto read_piece = [&](Frags &f, int g, int a_slot, int ks) {
         // the B part of a tile sits in the ring slot after its A part
         const int b_slot = a_slot + 1 < N_PARTS ? a_slot + 1 : 0;
-        if (g < 8)
-            f.v[g] = *reinterpret_cast<const bf16x8 *>(lds + b_slot * PART_BYTES + b_rd[ks] + (g >> 2) * (128 * 128) +
-                                                       (g & 3) * (16 * 128));
+        if (g < 2 * NB)
+            f.v[g] = *reinterpret_cast<const bf16x8 *>(lds + b_slot * PART_BYTES + b_rd[ks] + (g / NB) * (BNH * 128) +
+                                                       (g % NB) * (16 * 128));
         else
-            f.v[g] = *reinterpret_cast<const bf16x8 *>(lds + a_slot * PART_BYTES + a_rd[ks] + (g - 8) * (16 * 128));
+            f.v[g] = *reinterpret_cast<const bf16x8 *>(lds + a_slot * PART_BYTES + a_rd[ks] + (g - 2 * NB) * (16 * 128));
     };
     // kRowsAreB: the B rows (weights) are the MFMA's row operand and the A rows (tokens) its column
     // operand.  In the 16x16 result lane l then holds column l & 15 = one token and rows
     // 4 * (l >> 4) + 0..3 = four consecutive B rows, which the epilogues store as one 8- or 16-byte
     // piece of the token's output row.  Otherwise tokens are the rows.
     auto mfma_n = [&](const Frags &f, int m) {
-        const int i = m >> 3, b = m & 7;
-        const bf16x8 r = kRowsAreB ? f.v[b] : f.v[8 + i], c = kRowsAreB ? f.v[8 + i] : f.v[b];
-        if (b < 4) acc0[i][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r, c, acc0[i][b], 0, 0, 0);
-        else acc1[i][b - 4] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r, c, acc1[i][b - 4], 0, 0, 0);
+        const int i = m / (2 * NB), b = m % (2 * NB);
+        const bf16x8 r = kRowsAreB ? f.v[b] : f.v[2 * NB + i], c = kRowsAreB ? f.v[2 * NB + i] : f.v[b];
+        if (b < NB) acc0[i][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r, c, acc0[i][b], 0, 0, 0);
+        else acc1[i][b - NB] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r, c, acc1[i][b - NB], 0, 0, 0);
     };
     // One K step, written in the instruction order wanted: slots of {4 MFMAs, then LDS reads of
-    // the next step's fragments, then (every other slot) one direct load}; nothing may be
+    // the next step's fragments, then (in evenly spaced slots) one direct load}; nothing may be
     // moved across a slot boundary.  The compiler waits for ALL outstanding LDS reads before the
     // first MFMA of a step (direct-to-LDS loads in flight make it give up exact counting), so the
     // reads are packed into the early slots and the last slots leave them time to land.
@@ -262,10 +274,8 @@ __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, in
             __builtin_amdgcn_sched_barrier(0);
             if (2 * g < N_PIECES) read_piece(nxt_f, 2 * g, rd_slot, rd_ks);
             if (2 * g + 1 < N_PIECES) read_piece(nxt_f, 2 * g + 1, rd_slot, rd_ks);
-            if ((g & 1) == 0) {
-                if (dma == 1) dma_part(g / 2, pt, a_off);
-                if (dma == 2) dma_part(g / 2, pt, b_off);
-            }
+            if (dma == 1 && g % (N_SLOTS / PL) == 0) dma_part(g / (N_SLOTS / PL), pt, a_off);
+            if (dma == 2 && g % (N_SLOTS / PLB) == 0) dma_part(g / (N_SLOTS / PLB), pt, b_off);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -284,27 +294,27 @@ __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, in
     }
 #pragma unroll
     for (int p = 0; p < 2; ++p) {
-        const Part pa = part_of(qa, a_base), pb = part_of(qb, b_base);
+        const Part pa = part_of(qa, a_base, wa_dst), pb = part_of(qb, b_base, wb_dst);
 #pragma unroll
         for (int n = 0; n < PL; ++n) dma_part(n, pa, a_off);
 #pragma unroll
-        for (int n = 0; n < PL; ++n) dma_part(n, pb, b_off);
+        for (int n = 0; n < PLB; ++n) dma_part(n, pb, b_off);
         advance(qa);
         advance(qb);
     }
-    pipeline_barrier<2 * PL>();
+    pipeline_barrier<PL + PLB>();
     Frags f0, f1;
 #pragma unroll
     for (int g = 0; g < N_PIECES; ++g) read_piece(f0, g, 0, 0);
 
     int rd = 0;                                   // ring slot of the A part of the tile in use
     for (int it = 0; it < nk; ++it) {
-        const Part pa = part_of(qa, a_base);
+        const Part pa = part_of(qa, a_base, wa_dst);
         k_step(f0, f1, rd, 1, 1, pa);             // + A part of tile it+2
         advance(qa);
         pipeline_barrier<PL>();                   // tile it+1 has landed; tile it's slots are free
         rd = rd + 2 < N_PARTS ? rd + 2 : rd + 2 - N_PARTS;
-        const Part pb = part_of(qb, b_base);
+        const Part pb = part_of(qb, b_base, wb_dst);
         k_step(f1, f0, rd, 0, 2, pb);             // + B part of tile it+2
         advance(qb);
     }
@@ -354,13 +364,14 @@ __device__ __forceinline__ bool tile_of(int id, int tiles_m, int tiles_n, int &t
 }
 
 // grid.x = 8 * ids_per_xcd(tilesM * sum over runs of N tiles).
-template <int WM>
+template <int WM, int NB>
 __global__ void __launch_bounds__(WM * 128)
 gate_up_mfma(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
              const uint16_t *__restrict__ Wu, uint16_t *__restrict__ H, int T, int d_model, int d_inter,
              int ldh, int tiles_m, int tiles_n, BranchTable bt)
 {
     __shared__ __attribute__((aligned(1024))) char lds[LDS_BYTES];
+    constexpr int BNH = 32 * NB;                  // neurons per tile
     int tm, tn;
     if (!tile_of(blockIdx.x, tiles_m, tiles_n, tm, tn)) return;
     int n0 = 0, n_end = 0;
@@ -377,21 +388,21 @@ gate_up_mfma(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
     const int t0 = tm * BM;
 
     constexpr int MI = 16 / WM;
-    f32x4 accg[MI][4], accu[MI][4];
+    f32x4 accg[MI][NB], accu[MI][NB];
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < NB; ++j) {
             accg[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
             accu[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
 
     const int nk = (d_model + BK - 1) / BK;
-    mainloop<WM, true>(X + (size_t)t0 * d_model, d_model, T - t0, Wg + (size_t)n0 * d_model,
+    mainloop<WM, NB, true>(X + (size_t)t0 * d_model, d_model, T - t0, Wg + (size_t)n0 * d_model,
                        Wu + (size_t)n0 * d_model, d_model, n_end - n0, n_end - n0, KSingle{d_model}, 0, nk,
                        lds, accg, accu);
 
-    // alpha of the tile's 128 neurons -> LDS (the main loop is done with it)
+    // alpha of the tile's neurons -> LDS (the main loop is done with it)
     float *al = reinterpret_cast<float *>(lds);
     if (threadIdx.x < BNH) {
         const int n = n0 + threadIdx.x;
@@ -406,8 +417,8 @@ gate_up_mfma(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
     for (int i = 0; i < MI; ++i) {
         const int t = t0 + wm * (MI * 16) + i * 16 + tcol;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int nl = wn * 64 + j * 16 + 4 * q4;      // first of 4 neurons, tile relative
+        for (int j = 0; j < NB; ++j) {
+            const int nl = wn * (16 * NB) + j * 16 + 4 * q4;   // first of 4 neurons, tile relative
             // run ends are multiples of 8: the four neurons are all inside the run or all outside
             if (t < T && n0 + nl < n_end) {
                 const f32x4 a4 = *reinterpret_cast<const f32x4 *>(al + nl);
@@ -424,7 +435,7 @@ gate_up_mfma(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
 }
 
 // grid.x = splits * 8 * ids_per_xcd(tilesM * tilesN); dst = out (splits == 1) or partial[split][T][d_model].
-template <int WM>
+template <int WM, int NB>
 __global__ void __launch_bounds__(WM * 128)
 down_mfma(const uint16_t *__restrict__ H, const uint16_t *__restrict__ Wd, float *__restrict__ dst, int T,
           int d_model, int d_inter, int ldh, int tiles_m, int tiles_n, int splits, int kt_total,
@@ -435,23 +446,24 @@ down_mfma(const uint16_t *__restrict__ H, const uint16_t *__restrict__ Wd, float
     const int z = blockIdx.x / per_split;
     int tm, tn;
     if (!tile_of(blockIdx.x % per_split, tiles_m, tiles_n, tm, tn)) return;
+    constexpr int BNH = 32 * NB;                  // output features per B block; a tile has two
     const int t0 = tm * BM, n0 = tn * (2 * BNH);
     const int kt_begin = (int)((long long)kt_total * z / splits);
     const int kt_end = (int)((long long)kt_total * (z + 1) / splits);
 
     constexpr int MI = 16 / WM;
-    f32x4 acc0[MI][4], acc1[MI][4];
+    f32x4 acc0[MI][NB], acc1[MI][NB];
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < NB; ++j) {
             acc0[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
             acc1[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
 
-    // the second block of 128 output features may start past d_model: point it at the last row
+    // the second block of output features may start past d_model: point it at the last row
     const int n1 = n0 + BNH < d_model ? n0 + BNH : d_model - 1;
-    mainloop<WM, true>(H + (size_t)t0 * ldh, ldh, T - t0, Wd + (size_t)n0 * d_inter, Wd + (size_t)n1 * d_inter,
+    mainloop<WM, NB, true>(H + (size_t)t0 * ldh, ldh, T - t0, Wd + (size_t)n0 * d_inter, Wd + (size_t)n1 * d_inter,
                        d_inter, d_model - n0, d_model - n1, KRuns{bt}, kt_begin, kt_end, lds, acc0, acc1);
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -464,8 +476,8 @@ down_mfma(const uint16_t *__restrict__ H, const uint16_t *__restrict__ Wd, float
 #pragma unroll
         for (int half = 0; half < 2; ++half)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int m = n0 + half * BNH + wn * 64 + j * 16 + 4 * q4;
+            for (int j = 0; j < NB; ++j) {
+                const int m = n0 + half * BNH + wn * (16 * NB) + j * 16 + 4 * q4;
                 // d_model is a multiple of 8: the four features are all inside or all outside
                 if (t < T && m < d_model)
                     *reinterpret_cast<f32x4 *>(o + (size_t)t * d_model + m) = half ? acc1[i][j] : acc0[i][j];
@@ -492,11 +504,10 @@ int k_tiles(const BranchTable &bt)
     return n;
 }
 
-}  // namespace
-
-int mfma_down_splits(int T, int d_model, int k_elems)
+// Split-K factor of the down projection for output tiles of 256 x tile_n.
+int down_splits(int T, int d_model, int k_elems, int tile_n)
 {
-    const long long tiles = (long long)ceil_div(T, BM) * ceil_div(d_model, 2 * BNH);
+    const long long tiles = (long long)ceil_div(T, BM) * ceil_div(d_model, tile_n);
     const int kt = ceil_div(k_elems > 0 ? k_elems : 1, BK);
     long long s = 256 / tiles;
     if (s > kt / 4) s = kt / 4;
@@ -504,43 +515,77 @@ int mfma_down_splits(int T, int d_model, int k_elems)
     return s < 1 ? 1 : (int)s;
 }
 
+// Which tile width to use for `tiles` wide tiles on a chip that runs 256 at a time: narrow tiles
+// (half the neurons / output features) take about 0.55 of a wide tile's time, so they pay off when
+// the wide tiles' last round would be mostly empty.
+bool narrow_tiles_pay(long long wide_tiles)
+{
+    const long long rounds_wide = (wide_tiles + 255) / 256;
+    const double rounds_narrow = (double)((2 * wide_tiles + 255) / 256) * 0.55;
+    return rounds_narrow < (double)rounds_wide * 0.97;
+}
+
+}  // namespace
+
+int mfma_down_splits(int T, int d_model, int k_elems) { return down_splits(T, d_model, k_elems, 2 * BNH_MAX); }
+
 size_t mfma_partial_bytes(int T, int d_model, int d_inter)
 {
+    // sized for the wide tiles: narrow tiles double the tile count and so never split more
     const int s = mfma_down_splits(T, d_model, d_inter);
     return s > 1 ? align_up((size_t)s * T * d_model * sizeof(float), 256) : 0;
+}
+
+template <int NB>
+static hipError_t launch_gate_up(const FwdArgs &a, const BranchTable &bt, int tiles_m)
+{
+    long long tiles_n = 0;
+    for (int r = 0; r < bt.n_runs; ++r) tiles_n += ceil_div(bt.run_end[r] - bt.run_start[r], 32 * NB);
+    const long long grid = (long long)XCDS * ids_per_xcd(tiles_m * tiles_n);
+    if (grid > 0x7fffffffLL) return note_hip_error("gate_up_mfma grid", hipErrorInvalidValue);
+    ProfileScope ps(MLPMOE_KERNEL_GATE_UP_MFMA, a.stream);
+    gate_up_mfma<MFMA_WM, NB><<<(unsigned)grid, MFMA_WM * 128, 0, a.stream>>>(
+        static_cast<const uint16_t *>(a.x), static_cast<const uint16_t *>(a.Wg),
+        static_cast<const uint16_t *>(a.Wu), static_cast<uint16_t *>(a.H), a.T, a.d_model, a.d_inter,
+        a.ldh, tiles_m, (int)tiles_n, bt);
+    return launch_status("gate_up_mfma launch");
+}
+
+template <int NB>
+static hipError_t launch_down(const FwdArgs &a, const BranchTable &bt, int tiles_m, int kt_total, int *splits_out)
+{
+    const int tile_n = 64 * NB;
+    const int tiles_n = ceil_div(a.d_model, tile_n);
+    // splits from the active width: never more than the workspace was sized for (d_inter >= d_eff)
+    int splits = down_splits(a.T, a.d_model, bt.d_eff, tile_n);
+    if (splits > kt_total) splits = kt_total;
+    if (splits > 1 && (size_t)splits * a.T * a.d_model * sizeof(float) > a.partial_bytes) splits = 1;
+    const long long grid = (long long)XCDS * ids_per_xcd((long long)tiles_m * tiles_n) * splits;
+    if (grid > 0x7fffffffLL) return note_hip_error("down_mfma grid", hipErrorInvalidValue);
+    *splits_out = splits;
+    ProfileScope ps(MLPMOE_KERNEL_DOWN_MFMA, a.stream);
+    down_mfma<MFMA_WM, NB><<<(unsigned)grid, MFMA_WM * 128, 0, a.stream>>>(
+        static_cast<const uint16_t *>(a.H), static_cast<const uint16_t *>(a.Wd), splits > 1 ? a.partial : a.out,
+        a.T, a.d_model, a.d_inter, a.ldh, tiles_m, tiles_n, splits, kt_total, bt);
+    return launch_status("down_mfma launch");
 }
 
 hipError_t launch_mfma_bf16(const FwdArgs &a, const BranchTable &bt)
 {
     const int tiles_m = ceil_div(a.T, BM);
-    long long tiles_n1 = 0;
-    for (int r = 0; r < bt.n_runs; ++r) tiles_n1 += ceil_div(bt.run_end[r] - bt.run_start[r], BNH);
-    const long long grid1 = (long long)XCDS * ids_per_xcd(tiles_m * tiles_n1);
-    const int tiles_n2 = ceil_div(a.d_model, 2 * BNH);
-    // splits from the active width: never more than the workspace was sized for (d_inter >= d_eff)
-    int splits = mfma_down_splits(a.T, a.d_model, bt.d_eff);
-    const int kt_total = k_tiles(bt);
-    if (splits > kt_total) splits = kt_total;
-    if (splits > 1 && (size_t)splits * a.T * a.d_model * sizeof(float) > a.partial_bytes) splits = 1;
-    const long long grid2 = (long long)XCDS * ids_per_xcd((long long)tiles_m * tiles_n2) * splits;
-    if (grid1 > 0x7fffffffLL || grid2 > 0x7fffffffLL) return hipErrorInvalidValue;
+    long long wide1 = 0;
+    for (int r = 0; r < bt.n_runs; ++r) wide1 += ceil_div(bt.run_end[r] - bt.run_start[r], BNH_MAX);
+    wide1 *= tiles_m;
+    hipError_t e = narrow_tiles_pay(wide1) ? launch_gate_up<2>(a, bt, tiles_m) : launch_gate_up<4>(a, bt, tiles_m);
+    if (e != hipSuccess) return hipErrorLaunchFailure;
 
-    {
-    ProfileScope ps(MLPMOE_KERNEL_GATE_UP_MFMA, a.stream);
-    gate_up_mfma<MFMA_WM><<<(unsigned)grid1, MFMA_WM * 128, 0, a.stream>>>(
-        static_cast<const uint16_t *>(a.x), static_cast<const uint16_t *>(a.Wg),
-        static_cast<const uint16_t *>(a.Wu), static_cast<uint16_t *>(a.H), a.T, a.d_model, a.d_inter,
-        a.ldh, tiles_m, (int)tiles_n1, bt);
-    if (launch_status("gate_up_mfma launch") != hipSuccess) return hipErrorLaunchFailure;
-    }
-    float *dst = splits > 1 ? a.partial : a.out;
-    {
-    ProfileScope ps(MLPMOE_KERNEL_DOWN_MFMA, a.stream);
-    down_mfma<MFMA_WM><<<(unsigned)grid2, MFMA_WM * 128, 0, a.stream>>>(
-        static_cast<const uint16_t *>(a.H), static_cast<const uint16_t *>(a.Wd), dst, a.T, a.d_model,
-        a.d_inter, a.ldh, tiles_m, tiles_n2, splits, kt_total, bt);
-    if (launch_status("down_mfma launch") != hipSuccess) return hipErrorLaunchFailure;
-    }
+    const int kt_total = k_tiles(bt);
+    // the down projection fills the chip by splitting K; narrow tiles halve the partial sums that
+    // have to be written and added up again, so they pay whenever K is split
+    const bool narrow2 = down_splits(a.T, a.d_model, bt.d_eff, 2 * BNH_MAX) > 1;
+    int splits = 1;
+    e = narrow2 ? launch_down<2>(a, bt, tiles_m, kt_total, &splits) : launch_down<4>(a, bt, tiles_m, kt_total, &splits);
+    if (e != hipSuccess) return hipErrorLaunchFailure;
     if (splits > 1) {
         ProfileScope ps(MLPMOE_KERNEL_SPLITK_REDUCE, a.stream);
         const size_t n = (size_t)a.T * a.d_model;

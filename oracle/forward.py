@@ -39,6 +39,8 @@ def _load():
         bp = ctypes.POINTER(ctypes.c_uint8)
         lib.oracle_mlpmoe_forward.argtypes = [fp, fp, fp, fp, ip, fp, bp] + [ctypes.c_int] * 5 + [dp]
         lib.oracle_mlpmoe_forward.restype = ctypes.c_int
+        lib.oracle_mlpmoe_forward_routed.argtypes = [fp, fp, fp, fp, ip, fp, bp, bp] + [ctypes.c_int] * 5 + [dp]
+        lib.oracle_mlpmoe_forward_routed.restype = ctypes.c_int
         lib.oracle_dense_swiglu.argtypes = [fp, fp, fp, fp] + [ctypes.c_int] * 3 + [dp]
         lib.oracle_dense_swiglu.restype = ctypes.c_int
         lib.oracle_num_threads.restype = ctypes.c_int
@@ -85,6 +87,34 @@ def mlpmoe_forward(x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, 
                                        _ptr(out, ctypes.c_double))
     if rc != 0:
         raise ValueError("oracle_mlpmoe_forward rejected its arguments (rc=%d)" % rc)
+    return out
+
+
+def mlpmoe_forward_routed(x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, route, mode="exact"):
+    """The branched forward with a per-token branch set: token t sums the branches b with
+    active_mask[b] and route[t, b] nonzero (route: [T, B] uint8).  Same modes as mlpmoe_forward."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    T, d_model = x.shape
+    off = np.ascontiguousarray(branch_offsets, dtype=np.int32)
+    B = off.shape[0] - 1
+    d_inter = int(off[-1])
+    Wg = _f32(W_gate, (d_inter, d_model))
+    Wu = _f32(W_up, (d_inter, d_model))
+    Wd = _f32(W_down, (d_model, d_inter))
+    al = _f32(alpha, (B,))
+    mk = np.ascontiguousarray(active_mask, dtype=np.uint8)
+    rt = np.ascontiguousarray(route, dtype=np.uint8)
+    if mk.shape != (B,) or rt.shape != (T, B):
+        raise ValueError("active_mask must have B entries and route T x B")
+    out = np.empty((T, d_model), dtype=np.float64)
+    m = {"exact": 0, "contract": 1}[mode]
+    rc = _load().oracle_mlpmoe_forward_routed(_ptr(x, ctypes.c_float), _ptr(Wg, ctypes.c_float),
+                                              _ptr(Wu, ctypes.c_float), _ptr(Wd, ctypes.c_float),
+                                              _ptr(off, ctypes.c_int32), _ptr(al, ctypes.c_float),
+                                              _ptr(mk, ctypes.c_uint8), _ptr(rt, ctypes.c_uint8), T, d_model,
+                                              d_inter, B, m, _ptr(out, ctypes.c_double))
+    if rc != 0:
+        raise ValueError("oracle_mlpmoe_forward_routed rejected its arguments (rc=%d)" % rc)
     return out
 
 

@@ -130,6 +130,47 @@ int oracle_mlpmoe_forward(const float *x, const float *Wg, const float *Wu, cons
     return fail ? -2 : 0;
 }
 
+/*
+ * Per-token routing over branches (the paper names dynamic routing as the natural extension of the
+ * branch structure, Sec. 7 / Sec. 8, without defining it; reading taken here): every token t has
+ * its own set of branches, route[t*B + b] != 0, and
+ *     out_t = sum over { b : active[b] and route[t][b] } of alpha_b W_down^(b)[SiLU(W_gate^(b) x_t) (.) W_up^(b) x_t].
+ * That is the forward above with the branch mask replaced, token by token, by active AND route_t.
+ */
+int oracle_mlpmoe_forward_routed(const float *x, const float *Wg, const float *Wu, const float *Wd,
+                                 const int32_t *off, const float *alpha, const uint8_t *active,
+                                 const uint8_t *route, int T, int d_model, int d_inter, int B, int mode,
+                                 double *out)
+{
+    if (!x || !Wg || !Wu || !Wd || !off || !alpha || !active || !route || !out) return -1;
+    if (T < 0 || d_model <= 0 || d_inter < 0 || B <= 0 || B > 4096) return -1;
+    if (off[0] != 0 || off[B] != d_inter) return -1;
+    for (int b = 0; b < B; ++b)
+        if (off[b + 1] < off[b]) return -1;
+    int fail = 0;
+#pragma omp parallel
+    {
+        double *h = (double *)malloc(sizeof(double) * (size_t)(d_inter > 0 ? d_inter : 1));
+        uint8_t *eff = (uint8_t *)malloc((size_t)B);
+        if (!h || !eff) {
+#pragma omp atomic write
+            fail = 1;
+        }
+#pragma omp barrier
+        if (!fail) {
+#pragma omp for schedule(dynamic, 1)
+            for (int t = 0; t < T; ++t) {
+                for (int b = 0; b < B; ++b) eff[b] = (uint8_t)(active[b] && route[(size_t)t * B + b]);
+                forward_token(x + (size_t)t * d_model, Wg, Wu, Wd, off, alpha, eff, d_model, d_inter, B,
+                              mode, h, out + (size_t)t * d_model);
+            }
+        }
+        free(h);
+        free(eff);
+    }
+    return fail ? -2 : 0;
+}
+
 /* Dense SwiGLU MLP with no branch structure: W_down [ SiLU(W_gate x) (.) W_up x ]  (Sec. 2.2 identity,
  * right-hand side before slicing).  Kept separate from the branched code path on purpose. */
 int oracle_dense_swiglu(const float *x, const float *Wg, const float *Wu, const float *Wd,

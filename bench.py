@@ -225,6 +225,34 @@ def others(mm, synth, torch, seed):
                 sweep["K%d" % K] = row
             res["llama8b_first_k_sweep"] = sweep
             del sets, xs
+            # per-token routing, 4 of 16 branches per token: tokens grouped by route (each tile of 256
+            # tokens shares its 4 branches), random routes, and decode
+            rt = {}
+            xs = mm.bf16_tensor(synth.make_layer(name, 4096, seed=seed).x)
+            off16, _, mask16, _ = mm.mlpmoe_slice(w.d_inter, w.B)
+            rng = np.random.default_rng(seed)
+            grouped = np.zeros((4096, w.B), np.uint8)
+            for g in range(16):
+                for j in range(4):
+                    grouped[g * 256:(g + 1) * 256, (g + 3 * j) % w.B] = 1
+            rand = np.zeros((4096, w.B), np.uint8)
+            for t in range(4096):
+                rand[t, rng.choice(w.B, size=4, replace=False)] = 1
+            sets = [dev, [t.clone() for t in dev]]
+            for tag, route, T in (("grouped_T4096", grouped, 4096), ("random_T4096", rand, 4096),
+                                  ("top4_T1", rand, 1), ("top4_T16_same", grouped, 16)):
+                r = torch.from_numpy(np.ascontiguousarray(route[:T])).cuda()
+                xT = xs[:T].contiguous()
+                out = torch.empty((T, w.d_model), dtype=torch.float32, device="cuda")
+
+                def callr(i, xT=xT, out=out, r=r):
+                    Wg, Wu, Wd = sets[i % 2]
+                    mm.mlpmoe_forward_routed_bf16(xT, Wg, Wu, Wd, off16, alpha, mask16, r, out=out)
+
+                ms, _ = time_steps(mm, torch, callr, 20 if T > 16 else 50, 5, events=False)
+                rt[tag] = {"us_per_step": round(ms * 1e3, 2), "branches_per_token": 4}
+            res["llama8b_routed_4_of_16"] = rt
+            del sets, xs
             # Fractal Fade weight preparation (Sec. 3.2 schedule) on the same layer: the call is
             # synchronous (it returns thresholds), so wall-clock time around it is the cost
             best = None

@@ -192,6 +192,30 @@ MLPMOE_API int mlpmoe_forward_f32_ws(const float *x, const float *W_gate, const 
                           float *out, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * mlpmoe_forward_routed_bf16 / _ws -- the forward with a per-token set of branches.
+ *
+ * The paper names dynamic routing over the branches as the natural next step (Sec. 7, Sec. 8) and does
+ * not define it; the reading implemented here: route is a device array [T, B] of bytes, and token t
+ * sums the branches b with active_mask[b] != 0 AND route[t * B + b] != 0,
+ *     out[t] = sum over those b of alpha[b] * W_down^(b) [ SiLU(W_gate^(b) x_t) (.) W_up^(b) x_t ].
+ * All other arguments, layouts and rounding are those of mlpmoe_forward_bf16 (bf16 storage only).
+ * When every branch offset is a multiple of 8 (mlpmoe_slice with pad_to = 8) the kernels skip work
+ * per (tile of 256 tokens, branch) pair that no token of the tile is routed to -- for T <= 16 per
+ * branch no token takes, whose weights are then never read -- so tokens grouped by route make the
+ * call proportionally cheaper; other tables take the generic kernels, which only mask.
+ * The _ws form takes a caller-owned workspace of mlpmoe_workspace_bytes() bytes and never allocates.
+ */
+MLPMOE_API int mlpmoe_forward_routed_bf16(const void *x, const void *W_gate, const void *W_up,
+                                          const void *W_down, const int32_t *branch_offsets,
+                                          const float *alpha, const uint8_t *active_mask, const uint8_t *route,
+                                          int T, int d_model, int d_inter, int B, float *out, void *stream);
+MLPMOE_API int mlpmoe_forward_routed_bf16_ws(const void *x, const void *W_gate, const void *W_up,
+                                             const void *W_down, const int32_t *branch_offsets,
+                                             const float *alpha, const uint8_t *active_mask,
+                                             const uint8_t *route, int T, int d_model, int d_inter, int B,
+                                             float *out, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * mlpmoe_fade -- Fractal Fade weight preparation (Sec. 3.2), in place, on the device.
  *
  * For every branch b with sparsity[b] > 0, and separately for the branch's rows of W_gate and of

@@ -26,7 +26,7 @@ EXPORTS = ["mlpmoe_status_string", "mlpmoe_last_error_detail", "mlpmoe_slice", "
            "mlpmoe_forward_bf16", "mlpmoe_forward", "mlpmoe_forward_f32", "mlpmoe_forward_bf16_ws",
            "mlpmoe_forward_f32_ws", "mlpmoe_release", "mlpmoe_profile_enable",
            "mlpmoe_profile_collect", "mlpmoe_profile_disable", "mlpmoe_plan_create", "mlpmoe_plan_forward",
-           "mlpmoe_plan_destroy"]
+           "mlpmoe_plan_destroy", "mlpmoe_forward_routed_bf16", "mlpmoe_forward_routed_bf16_ws"]
 
 
 class MlpMoeError(RuntimeError):
@@ -67,6 +67,10 @@ def _load() -> ctypes.CDLL:
     lib.mlpmoe_plan_forward.restype = i
     lib.mlpmoe_plan_destroy.argtypes = [vp]
     lib.mlpmoe_plan_destroy.restype = i
+    lib.mlpmoe_forward_routed_bf16.argtypes = [vp, vp, vp, vp, ip, fp, bp, vp, i, i, i, i, vp, vp]
+    lib.mlpmoe_forward_routed_bf16.restype = i
+    lib.mlpmoe_forward_routed_bf16_ws.argtypes = [vp, vp, vp, vp, ip, fp, bp, vp, i, i, i, i, vp, vp, sz, vp]
+    lib.mlpmoe_forward_routed_bf16_ws.restype = i
     lib.mlpmoe_fade.argtypes = [vp, vp, ip, vp, i, i, i, i, vp, vp, vp]
     lib.mlpmoe_fade.restype = i
     lib.mlpmoe_workspace_bytes.argtypes = [i, i, i, i, i]
@@ -243,6 +247,28 @@ def mlpmoe_forward_f32_ws(x, W_gate, W_up, W_down, branch_offsets, alpha, active
 
 def mlpmoe_release():
     _check(lib.mlpmoe_release(), "mlpmoe_release")
+
+
+def mlpmoe_forward_routed_bf16(x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, route, out=None,
+                               workspace=None, stream=None):
+    """Forward with a per-token branch set: route is a [T, B] uint8 GPU tensor (nonzero = token takes branch)."""
+    import torch
+    off, al, mk, B = _table(branch_offsets, alpha, active_mask)
+    T, d_model = int(x.shape[0]), int(x.shape[1])
+    d_inter = int(off[-1])
+    if route.dtype != torch.uint8 or tuple(route.shape) != (T, B):
+        raise ValueError("route must be a [T, B] uint8 tensor")
+    if out is None:
+        out = torch.empty((T, d_model), dtype=torch.float32, device=x.device)
+    common = (_dev_ptr(x), _dev_ptr(W_gate), _dev_ptr(W_up), _dev_ptr(W_down), off.ctypes.data, al.ctypes.data,
+              mk.ctypes.data, _dev_ptr(route) if T else None, T, d_model, d_inter, B, _dev_ptr(out))
+    if workspace is None:
+        rc = lib.mlpmoe_forward_routed_bf16(*common, _stream_ptr(stream))
+        _check(rc, "mlpmoe_forward_routed_bf16")
+    else:
+        rc = lib.mlpmoe_forward_routed_bf16_ws(*common, _dev_ptr(workspace), int(workspace.numel()), _stream_ptr(stream))
+        _check(rc, "mlpmoe_forward_routed_bf16_ws")
+    return out
 
 
 class Plan:

@@ -34,6 +34,8 @@ struct FwdArgs {
     int ldh;
     float *partial;     // split-K partial sums, or nullptr
     size_t partial_bytes;
+    const uint8_t *route = nullptr;   // per-token routing [T, B] (device), or nullptr
+    uint8_t *tile_need = nullptr;     // [ceil(T / 256), B] scratch of the routed paths (device)
     hipStream_t stream;
 };
 
@@ -68,7 +70,10 @@ size_t mfma_partial_bytes(int T, int d_model, int d_inter);
 hipError_t launch_fill_zero(float *out, size_t n, hipStream_t s);
 hipError_t launch_generic(const FwdArgs &a, const BranchTable &bt, bool is_bf16);
 hipError_t launch_mfma_bf16(const FwdArgs &a, const BranchTable &bt);
+hipError_t launch_route_tile_need(const FwdArgs &a, const BranchTable &bt);
+hipError_t launch_mfma_routed_bf16(const FwdArgs &a, const BranchTable &bt);
 hipError_t launch_decode_bf16(const FwdArgs &a, const BranchTable &bt);
+hipError_t launch_decode_routed_bf16(const FwdArgs &a, const BranchTable &bt);
 hipError_t launch_compact(const void *Wg, const void *Wu, const void *Wd, const int32_t *gather,
                           int n_rows, int d_model, int d_inter_src, int elem_bytes, void *Wg_c,
                           void *Wu_c, void *Wd_c, hipStream_t s);

@@ -66,35 +66,77 @@ __device__ __forceinline__ int branch_of(const BranchTable &bt, int j)
 // Memory-level parallelism: every wave keeps the loads of U of its K blocks in flight (a ring of
 // U register sets: block i is consumed, then the load of block i+U is issued into its place).
 // All loads are branch free: a lane with nothing to load points at a zero chunk instead.
-template <int NW, int U, bool kGateUp>
+// Per-token routing (T <= 16): the set of branches some token of the batch takes, as a 64-bit
+// word, folded with the active mask.  Every wave works it out for itself from route[T, B]: lane b
+// looks down column b.
+__device__ __forceinline__ unsigned long long live_branches(const BranchTable &bt, const uint8_t *route, int T)
+{
+    const int b = threadIdx.x & 63;
+    bool any = false;
+    if (b < bt.B)
+        for (int t = 0; t < T; ++t) any = any || route[(size_t)t * bt.B + b] != 0;
+    return __ballot(any) & bt.active;
+}
+
+// The stretches of the intermediate dimension a launch works on.  Without routing they are the
+// table's runs of active branches; with routing, one stretch per branch, empty unless the branch is
+// live (all branch offsets are then multiples of 8).
+template <bool kRouted>
+struct Stretches {
+    const BranchTable &bt;
+    unsigned long long live;
+    __device__ __forceinline__ int count() const { return kRouted ? bt.B : bt.n_runs; }
+    __device__ __forceinline__ int beg(int r) const { return kRouted ? bt.off[r] : bt.run_start[r]; }
+    __device__ __forceinline__ int end(int r) const
+    {
+        if (!kRouted) return bt.run_end[r];
+        return ((live >> r) & 1ULL) ? bt.off[r + 1] : bt.off[r];
+    }
+};
+
+// Walks the groups of 8 rows ("tiles") of the stretches in steps: (stretch, tile inside it).
+template <bool kRouted>
+struct TileCursor {
+    int r, t;
+    __device__ __forceinline__ TileCursor(const Stretches<kRouted> &st, int tile) : r(0), t(tile) { settle(st); }
+    __device__ __forceinline__ void settle(const Stretches<kRouted> &st)
+    {
+        while (r < st.count()) {
+            const int n = (st.end(r) - st.beg(r)) / 8;   // stretch lengths are multiples of 8
+            if (t < n) break;
+            t -= n;
+            ++r;
+        }
+    }
+    __device__ __forceinline__ void advance(const Stretches<kRouted> &st, int step)
+    {
+        t += step;
+        settle(st);
+    }
+    // first row of the tile under the cursor, -1 past the last tile
+    __device__ __forceinline__ int row0(const Stretches<kRouted> &st) const { return r < st.count() ? st.beg(r) + t * 8 : -1; }
+};
+
+template <int NW, int U, bool kGateUp, bool kRouted = false>
 __global__ void __launch_bounds__(NW * 64)
 decode_kernel(const uint16_t *__restrict__ Xin, int ldx, int T,
               const uint16_t *__restrict__ W0, const uint16_t *__restrict__ W1, int ldw,
               int d_model, uint16_t *__restrict__ Hout, int ldh, float *__restrict__ out,
-              BranchTable bt)
+              const uint8_t *__restrict__ route, BranchTable bt)
 {
     static_assert(NW >= 4, "the final reduction uses 256 threads");
     __shared__ float red[NW][256];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int r16 = lane & 15, q = lane >> 4;
+    const Stretches<kRouted> st{bt, kRouted ? live_branches(bt, route, T) : 0ULL};
 
     // tile -> this lane's weight row
     int row0 = 0;
     const uint16_t *wrow;
     if (kGateUp) {
-        int tile = blockIdx.x;
-        int found = 0;
-        for (int r = 0; r < bt.n_runs; ++r) {
-            const int n = (bt.run_end[r] - bt.run_start[r]) / 8;     // run lengths are multiples of 8
-            if (tile < n) {
-                row0 = bt.run_start[r] + tile * 8;
-                found = 1;
-                break;
-            }
-            tile -= n;
-        }
-        if (!found) return;
+        row0 = TileCursor<kRouted>(st, blockIdx.x).row0(st);
+        if (row0 < 0) return;                            // with routing the grid covers all active rows
         wrow = (r16 < 8 ? W0 : W1) + (size_t)(row0 + (r16 & 7)) * ldw;
     } else {
         row0 = blockIdx.x * 16;
@@ -108,9 +150,9 @@ decode_kernel(const uint16_t *__restrict__ Xin, int ldx, int T,
     const uint16_t *zero = reinterpret_cast<const uint16_t *>(g_zero16);
 
     // cursor over this wave's blocks: (range, block inside the range); ranges laid end to end
-    const int n_ranges = kGateUp ? 1 : bt.n_runs;
-    auto rbeg = [&](int r) { return kGateUp ? 0 : bt.run_start[r]; };
-    auto rend = [&](int r) { return kGateUp ? d_model : bt.run_end[r]; };
+    const int n_ranges = kGateUp ? 1 : st.count();
+    auto rbeg = [&](int r) { return kGateUp ? 0 : st.beg(r); };
+    auto rend = [&](int r) { return kGateUp ? d_model : st.end(r); };
     int cr = 0, cb = wave;                               // load cursor
     auto settle = [&]() {                                // move past ranges the block index overshoots
         while (cr < n_ranges) {
@@ -178,8 +220,10 @@ decode_kernel(const uint16_t *__restrict__ Xin, int ldx, int T,
             up += red[w][threadIdx.x + 32];              // row + 8: two lane groups further
         }
         const int n = row0 + row;
-        const float al = bt.alpha[branch_of(bt, n)];
-        Hout[(size_t)t * ldh + n] = to_bf16(al * silu_mul(g, up));
+        const int b = branch_of(bt, n);
+        float v = bt.alpha[b] * silu_mul(g, up);
+        if (kRouted) v = route[(size_t)t * bt.B + b] ? v : 0.f;
+        Hout[(size_t)t * ldh + n] = to_bf16(v);
     } else {
         float s0 = 0.f;
 #pragma unroll
@@ -199,11 +243,11 @@ decode_kernel(const uint16_t *__restrict__ Xin, int ldx, int T,
 // reduction buffer is double buffered).  Each wave's block count per tile is padded to a
 // multiple of U with blocks that read a zero chunk, which keeps ring slots compile-time constants.
 // x rows are padded by 16 bytes so that the 16 token rows of a fragment fall on distinct banks.
-template <int NW, int U>
+template <int NW, int U, bool kRouted = false>
 __global__ void __launch_bounds__(NW * 64)
 decode_gate_up_persist(const uint16_t *__restrict__ X, int T, const uint16_t *__restrict__ Wg,
                        const uint16_t *__restrict__ Wu, int d_model, uint16_t *__restrict__ Hout, int ldh,
-                       int tiles, BranchTable bt)
+                       const uint8_t *__restrict__ route, BranchTable bt)
 {
     static_assert(NW >= 4, "the reduction uses 256 threads");
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -222,30 +266,26 @@ decode_gate_up_persist(const uint16_t *__restrict__ X, int T, const uint16_t *__
     const size_t lane_row_off = (size_t)(r16 & 7) * d_model + q * 16;
     const uint16_t *wsel = r16 < 8 ? Wg : Wu;
 
-    auto tile_row0 = [&](int tile) {
-        int tt = tile;
-        for (int r = 0; r < bt.n_runs; ++r) {
-            const int n = (bt.run_end[r] - bt.run_start[r]) / 8;
-            if (tt < n) return bt.run_start[r] + tt * 8;
-            tt -= n;
-        }
-        return -1;
-    };
+    // with routing the workgroups share out the tiles of the live branches only
+    const Stretches<kRouted> st{bt, kRouted ? live_branches(bt, route, T) : 0ULL};
 
     // load cursor: U blocks ahead of the block being consumed
-    int l_tile = blockIdx.x, l_j = 0;
-    const uint16_t *l_wrow = wsel + (size_t)tile_row0(l_tile) * d_model + lane_row_off;
+    TileCursor<kRouted> l_cur(st, blockIdx.x);
+    int l_j = 0;
+    int l_row0 = l_cur.row0(st);
+    const uint16_t *l_wrow = wsel + (size_t)(l_row0 < 0 ? 0 : l_row0) * d_model + lane_row_off;
     u32x4 wa[U][2];
     auto load_next = [&](int u) {
         const int b = wave + NW * l_j;                   // K block inside the tile
         const int kl = b * KB + q * 16;
-        const bool live = l_tile < tiles;
-        wa[u][0] = ld16((live && kl < d_model) ? l_wrow + b * KB : zero);
-        wa[u][1] = ld16((live && kl + 8 < d_model) ? l_wrow + b * KB + 8 : zero);
+        const bool more = l_row0 >= 0;
+        wa[u][0] = ld16((more && kl < d_model) ? l_wrow + b * KB : zero);
+        wa[u][1] = ld16((more && kl + 8 < d_model) ? l_wrow + b * KB + 8 : zero);
         if (++l_j == nb_pad) {
             l_j = 0;
-            l_tile += gridDim.x;
-            if (l_tile < tiles) l_wrow = wsel + (size_t)tile_row0(l_tile) * d_model + lane_row_off;
+            l_cur.advance(st, gridDim.x);
+            l_row0 = l_cur.row0(st);
+            if (l_row0 >= 0) l_wrow = wsel + (size_t)l_row0 * d_model + lane_row_off;
         }
     };
 #pragma unroll
@@ -275,7 +315,8 @@ decode_gate_up_persist(const uint16_t *__restrict__ X, int T, const uint16_t *__
     __syncthreads();
 
     int it = 0;
-    for (int tile = blockIdx.x; tile < tiles; tile += gridDim.x, ++it) {
+    TileCursor<kRouted> cur(st, blockIdx.x);
+    for (int row0 = cur.row0(st); row0 >= 0; cur.advance(st, gridDim.x), row0 = cur.row0(st), ++it) {
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
         for (int j0 = 0; j0 < nb_pad; j0 += U) {
 #pragma unroll
@@ -307,9 +348,11 @@ decode_gate_up_persist(const uint16_t *__restrict__ X, int T, const uint16_t *__
                     g += rb[w * 256 + threadIdx.x];
                     up += rb[w * 256 + threadIdx.x + 32];
                 }
-                const int n = tile_row0(tile) + row;
-                const float al = bt.alpha[branch_of(bt, n)];
-                Hout[(size_t)r16 * ldh + n] = to_bf16(al * silu_mul(g, up));
+                const int n = row0 + row;
+                const int b = branch_of(bt, n);
+                float v = bt.alpha[b] * silu_mul(g, up);
+                if (kRouted) v = route[(size_t)r16 * bt.B + b] ? v : 0.f;
+                Hout[(size_t)r16 * ldh + n] = to_bf16(v);
             }
         }
     }
@@ -338,7 +381,8 @@ constexpr size_t kStreamLdsMax = 160 * 1024;
 
 }  // namespace
 
-hipError_t launch_decode_bf16(const FwdArgs &a, const BranchTable &bt)
+template <bool kRouted>
+static hipError_t launch_decode_impl(const FwdArgs &a, const BranchTable &bt)
 {
     long long tiles1 = 0;
     for (int r = 0; r < bt.n_runs; ++r) tiles1 += (bt.run_end[r] - bt.run_start[r]) / 8;
@@ -350,7 +394,7 @@ hipError_t launch_decode_bf16(const FwdArgs &a, const BranchTable &bt)
     if (xs_bytes <= kStreamLdsMax) {
         // per device, set up on the first call there: CU count and the kernel's LDS limit
         static std::mutex mu;
-        static int cus_of[64] = {0};
+        static int cus_of[64] = {0};              // one table per instantiation (attribute is per kernel)
         int dev = 0;
         hipError_t e = hipGetDevice(&dev);
         if (e != hipSuccess) return note_hip_error("hipGetDevice", e);
@@ -363,7 +407,7 @@ hipError_t launch_decode_bf16(const FwdArgs &a, const BranchTable &bt)
                 e = hipGetDeviceProperties(&prop, dev);
                 if (e != hipSuccess) return note_hip_error("hipGetDeviceProperties", e);
                 e = hipFuncSetAttribute(
-                    reinterpret_cast<const void *>(&decode_gate_up_persist<MLPMOE_DEC_SNW, MLPMOE_DEC_SU>),
+                    reinterpret_cast<const void *>(&decode_gate_up_persist<MLPMOE_DEC_SNW, MLPMOE_DEC_SU, kRouted>),
                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kStreamLdsMax);
                 if (e != hipSuccess) return note_hip_error("hipFuncSetAttribute(decode_gate_up_persist)", e);
                 cus_of[dev] = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 1;
@@ -372,27 +416,32 @@ hipError_t launch_decode_bf16(const FwdArgs &a, const BranchTable &bt)
         }
         const int grid = tiles1 < n_cus ? (int)tiles1 : n_cus;
         ProfileScope ps(MLPMOE_KERNEL_DECODE_GATE_UP, a.stream);
-        decode_gate_up_persist<MLPMOE_DEC_SNW, MLPMOE_DEC_SU><<<grid, MLPMOE_DEC_SNW * 64, xs_bytes, a.stream>>>(
+        decode_gate_up_persist<MLPMOE_DEC_SNW, MLPMOE_DEC_SU, kRouted><<<grid, MLPMOE_DEC_SNW * 64, xs_bytes, a.stream>>>(
             X, a.T, static_cast<const uint16_t *>(a.Wg), static_cast<const uint16_t *>(a.Wu), a.d_model, H,
-            a.ldh, (int)tiles1, bt);
+            a.ldh, a.route, bt);
         if (launch_status("decode_gate_up_persist launch") != hipSuccess) return hipErrorLaunchFailure;
     } else {
         ProfileScope ps(MLPMOE_KERNEL_DECODE_GATE_UP, a.stream);
-        decode_kernel<MLPMOE_DEC_NW1, MLPMOE_DEC_U1, true><<<(unsigned)tiles1, MLPMOE_DEC_NW1 * 64, 0, a.stream>>>(
+        decode_kernel<MLPMOE_DEC_NW1, MLPMOE_DEC_U1, true, kRouted><<<(unsigned)tiles1, MLPMOE_DEC_NW1 * 64, 0, a.stream>>>(
             X, a.d_model, a.T, static_cast<const uint16_t *>(a.Wg), static_cast<const uint16_t *>(a.Wu),
-            a.d_model, a.d_model, H, a.ldh, nullptr, bt);
+            a.d_model, a.d_model, H, a.ldh, nullptr, a.route, bt);
         if (launch_status("decode gate_up launch") != hipSuccess) return hipErrorLaunchFailure;
     }
     ProfileScope ps(MLPMOE_KERNEL_DECODE_DOWN, a.stream);
     if (tiles2 >= 192)
-        decode_kernel<MLPMOE_DEC_NW2, MLPMOE_DEC_U2, false><<<tiles2, MLPMOE_DEC_NW2 * 64, 0, a.stream>>>(
+        decode_kernel<MLPMOE_DEC_NW2, MLPMOE_DEC_U2, false, kRouted><<<tiles2, MLPMOE_DEC_NW2 * 64, 0, a.stream>>>(
             H, a.ldh, a.T, static_cast<const uint16_t *>(a.Wd), nullptr, a.d_inter, a.d_model, nullptr,
-            a.ldh, a.out, bt);
+            a.ldh, a.out, a.route, bt);
     else
-        decode_kernel<16, 4, false><<<tiles2, 1024, 0, a.stream>>>(
+        decode_kernel<16, 4, false, kRouted><<<tiles2, 1024, 0, a.stream>>>(
             H, a.ldh, a.T, static_cast<const uint16_t *>(a.Wd), nullptr, a.d_inter, a.d_model, nullptr,
-            a.ldh, a.out, bt);
+            a.ldh, a.out, a.route, bt);
     return launch_status("decode_down launch");
 }
+
+hipError_t launch_decode_bf16(const FwdArgs &a, const BranchTable &bt) { return launch_decode_impl<false>(a, bt); }
+
+// Per-token routing, T <= 16: the kernels read a.route themselves; a.tile_need is not used.
+hipError_t launch_decode_routed_bf16(const FwdArgs &a, const BranchTable &bt) { return launch_decode_impl<true>(a, bt); }
 
 }  // namespace mlpmoe

@@ -42,8 +42,10 @@ __device__ __forceinline__ int branch_of(const BranchTable &bt, int j)
 template <typename TIn, typename TH>
 __global__ void __launch_bounds__(GTHREADS)
 gate_up_generic(const TIn *__restrict__ X, const TIn *__restrict__ Wg, const TIn *__restrict__ Wu,
-                TH *__restrict__ H, int T, int K, int d_inter, int ldh, BranchTable bt)
+                TH *__restrict__ H, int T, int K, int d_inter, int ldh, const uint8_t *__restrict__ route,
+                BranchTable bt)
 {
+    // route (may be null): per-token routing [T, B]; H is 0 where a token does not take a branch
     __shared__ float Xs[GK][GT + 1], Gs[GK][GT + 1], Us[GK][GT + 1];
     const int t0 = blockIdx.y * GT, n0 = blockIdx.x * GT;
     // skip tiles that hold no active neuron
@@ -97,7 +99,9 @@ gate_up_generic(const TIn *__restrict__ X, const TIn *__restrict__ Wg, const TIn
             if (t >= T) continue;
             const float gg = g[i][j];
             const float s = gg / (1.0f + expf(-gg));
-            store_h(H, (size_t)t * ldh + n, al * (s * u[i][j]));
+            float v = al * (s * u[i][j]);
+            if (route && !route[(size_t)t * bt.B + b]) v = 0.f;
+            store_h(H, (size_t)t * ldh + n, v);
         }
     }
 }
@@ -228,7 +232,7 @@ hipError_t launch_generic_typed(const FwdArgs &a, const BranchTable &bt)
     ProfileScope ps(MLPMOE_KERNEL_GATE_UP_GENERIC, a.stream);
     gate_up_generic<TIn, TH><<<g1, GTHREADS, 0, a.stream>>>(
         static_cast<const TIn *>(a.x), static_cast<const TIn *>(a.Wg), static_cast<const TIn *>(a.Wu),
-        static_cast<TH *>(a.H), a.T, a.d_model, a.d_inter, a.ldh, bt);
+        static_cast<TH *>(a.H), a.T, a.d_model, a.d_inter, a.ldh, a.route, bt);
     }
     ProfileScope ps(MLPMOE_KERNEL_DOWN_GENERIC, a.stream);
     down_generic<TIn, TH><<<g2, GTHREADS, 0, a.stream>>>(

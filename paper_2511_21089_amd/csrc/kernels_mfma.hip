@@ -78,6 +78,38 @@ struct KRuns {
     __device__ __forceinline__ int end(int r) const { return bt.run_end[r]; }
 };
 
+// K ranges chosen per workgroup at run time (per-token routing: the branches some token of this
+// token tile is routed to).  Lane r of every wave holds the bounds of range r; reading them is a
+// lane read, not a memory access.
+struct KRunsLanes {
+    int n, v_start, v_end;
+    __device__ __forceinline__ int n_runs() const { return n; }
+    __device__ __forceinline__ int start(int r) const { return __builtin_amdgcn_readlane(v_start, r); }
+    __device__ __forceinline__ int end(int r) const { return __builtin_amdgcn_readlane(v_end, r); }
+};
+
+// Merged ranges of the branches that are active AND flagged in `needed` (B bytes, uniform).
+__device__ __forceinline__ KRunsLanes routed_runs(const BranchTable &bt, const uint8_t *needed)
+{
+    KRunsLanes kr{0, 0, 0};
+    const int lane = threadIdx.x & 63;
+    int prev_end = -1;
+    for (int b = 0; b < bt.B; ++b) {
+        if (!((bt.active >> b) & 1ULL) || !needed[b]) continue;
+        const int s = bt.off[b], e = bt.off[b + 1];
+        if (e == s) continue;
+        if (kr.n > 0 && prev_end == s) {
+            kr.v_end = lane == kr.n - 1 ? e : kr.v_end;
+        } else {
+            kr.v_start = lane == kr.n ? s : kr.v_start;
+            kr.v_end = lane == kr.n ? e : kr.v_end;
+            ++kr.n;
+        }
+        prev_end = e;
+    }
+    return kr;
+}
+
 template <typename KR>
 __device__ __forceinline__ KCursor k_seek(const KR &kr, int tile)
 {
@@ -364,11 +396,16 @@ __device__ __forceinline__ bool tile_of(int id, int tiles_m, int tiles_n, int &t
 }
 
 // grid.x = 8 * ids_per_xcd(tilesM * sum over runs of N tiles).
-template <int WM, int NB>
+// kRouted: per-token routing.  route[t * B + b] != 0 says token t takes branch b; tile_need[tm * B + b]
+// != 0 says some token of token tile tm does.  A tile none of whose branches is needed is skipped
+// (the down projection skips the same (token tile, branch) pairs), and H is multiplied by the
+// token's route bit, so that it is exactly 0 where a token does not take a branch.
+template <int WM, int NB, bool kRouted>
 __global__ void __launch_bounds__(WM * 128)
 gate_up_mfma(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
              const uint16_t *__restrict__ Wu, uint16_t *__restrict__ H, int T, int d_model, int d_inter,
-             int ldh, int tiles_m, int tiles_n, BranchTable bt)
+             int ldh, int tiles_m, int tiles_n, const uint8_t *__restrict__ route,
+             const uint8_t *__restrict__ tile_need, BranchTable bt)
 {
     __shared__ __attribute__((aligned(1024))) char lds[LDS_BYTES];
     constexpr int BNH = 32 * NB;                  // neurons per tile
@@ -386,6 +423,13 @@ gate_up_mfma(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
     }
     if (n_end == 0) return;
     const int t0 = tm * BM;
+    if (kRouted) {
+        const int n1 = n0 + BNH < n_end ? n0 + BNH : n_end;
+        bool any = false;
+        for (int b = branch_of(bt, n0); b < bt.B && bt.off[b] < n1; ++b)
+            any = any || (((bt.active >> b) & 1ULL) && tile_need[tm * bt.B + b]);
+        if (!any) return;
+    }
 
     constexpr int MI = 16 / WM;
     f32x4 accg[MI][NB], accu[MI][NB];
@@ -404,9 +448,12 @@ gate_up_mfma(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
 
     // alpha of the tile's neurons -> LDS (the main loop is done with it)
     float *al = reinterpret_cast<float *>(lds);
+    int *bl = reinterpret_cast<int *>(lds + BNH_MAX * sizeof(float));      // branch of each neuron (routing)
     if (threadIdx.x < BNH) {
         const int n = n0 + threadIdx.x;
-        al[threadIdx.x] = n < n_end ? bt.alpha[branch_of(bt, n)] : 0.f;
+        const int b = branch_of(bt, n < n_end ? n : n_end - 1);
+        al[threadIdx.x] = n < n_end ? bt.alpha[b] : 0.f;
+        if (kRouted) bl[threadIdx.x] = b;
     }
     __syncthreads();
 
@@ -424,7 +471,11 @@ gate_up_mfma(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
                 const f32x4 a4 = *reinterpret_cast<const f32x4 *>(al + nl);
                 uint16_t h[4];
 #pragma unroll
-                for (int q = 0; q < 4; ++q) h[q] = to_bf16(a4[q] * silu_mul(accg[i][j][q], accu[i][j][q]));
+                for (int q = 0; q < 4; ++q) {
+                    float v = a4[q] * silu_mul(accg[i][j][q], accu[i][j][q]);
+                    if (kRouted) v = route[(size_t)t * bt.B + bl[nl + q]] ? v : 0.f;
+                    h[q] = to_bf16(v);
+                }
                 u32x2 pk;
                 pk.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
                 pk.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
@@ -435,11 +486,13 @@ gate_up_mfma(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
 }
 
 // grid.x = splits * 8 * ids_per_xcd(tilesM * tilesN); dst = out (splits == 1) or partial[split][T][d_model].
-template <int WM, int NB>
+// kRouted: the K loop of token tile tm walks only the branches some token of the tile is routed
+// to (tile_need); H is 0 for the tokens of the tile that do not take a branch.
+template <int WM, int NB, bool kRouted>
 __global__ void __launch_bounds__(WM * 128)
 down_mfma(const uint16_t *__restrict__ H, const uint16_t *__restrict__ Wd, float *__restrict__ dst, int T,
           int d_model, int d_inter, int ldh, int tiles_m, int tiles_n, int splits, int kt_total,
-          BranchTable bt)
+          const uint8_t *__restrict__ tile_need, BranchTable bt)
 {
     __shared__ __attribute__((aligned(1024))) char lds[LDS_BYTES];
     const int per_split = XCDS * ids_per_xcd((long long)tiles_m * tiles_n);
@@ -448,6 +501,12 @@ down_mfma(const uint16_t *__restrict__ H, const uint16_t *__restrict__ Wd, float
     if (!tile_of(blockIdx.x % per_split, tiles_m, tiles_n, tm, tn)) return;
     constexpr int BNH = 32 * NB;                  // output features per B block; a tile has two
     const int t0 = tm * BM, n0 = tn * (2 * BNH);
+    KRunsLanes dyn{0, 0, 0};
+    if (kRouted) {
+        dyn = routed_runs(bt, tile_need + (size_t)tm * bt.B);
+        kt_total = 0;
+        for (int r = 0; r < dyn.n; ++r) kt_total += (dyn.end(r) - dyn.start(r) + BK - 1) / BK;
+    }
     const int kt_begin = (int)((long long)kt_total * z / splits);
     const int kt_end = (int)((long long)kt_total * (z + 1) / splits);
 
@@ -463,8 +522,14 @@ down_mfma(const uint16_t *__restrict__ H, const uint16_t *__restrict__ Wd, float
 
     // the second block of output features may start past d_model: point it at the last row
     const int n1 = n0 + BNH < d_model ? n0 + BNH : d_model - 1;
-    mainloop<WM, NB, true>(H + (size_t)t0 * ldh, ldh, T - t0, Wd + (size_t)n0 * d_inter, Wd + (size_t)n1 * d_inter,
-                       d_inter, d_model - n0, d_model - n1, KRuns{bt}, kt_begin, kt_end, lds, acc0, acc1);
+    if (kRouted)
+        mainloop<WM, NB, true>(H + (size_t)t0 * ldh, ldh, T - t0, Wd + (size_t)n0 * d_inter,
+                               Wd + (size_t)n1 * d_inter, d_inter, d_model - n0, d_model - n1, dyn, kt_begin, kt_end,
+                               lds, acc0, acc1);
+    else
+        mainloop<WM, NB, true>(H + (size_t)t0 * ldh, ldh, T - t0, Wd + (size_t)n0 * d_inter,
+                               Wd + (size_t)n1 * d_inter, d_inter, d_model - n0, d_model - n1, KRuns{bt}, kt_begin,
+                               kt_end, lds, acc0, acc1);
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -482,6 +547,18 @@ down_mfma(const uint16_t *__restrict__ H, const uint16_t *__restrict__ Wd, float
                 if (t < T && m < d_model)
                     *reinterpret_cast<f32x4 *>(o + (size_t)t * d_model + m) = half ? acc1[i][j] : acc0[i][j];
             }
+    }
+}
+
+// tile_need[tm * B + b] = 1 if some token of token tile tm (256 tokens) is routed to branch b.
+__global__ void __launch_bounds__(256)
+route_tile_need(const uint8_t *__restrict__ route, uint8_t *__restrict__ tile_need, int T, int B)
+{
+    const int t = blockIdx.x * BM + threadIdx.x;
+    for (int b = 0; b < B; ++b) {
+        const int mine = t < T ? route[(size_t)t * B + b] != 0 : 0;
+        const int any = __syncthreads_or(mine);
+        if (threadIdx.x == 0) tile_need[blockIdx.x * B + b] = (uint8_t)(any != 0);
     }
 }
 
@@ -536,7 +613,7 @@ size_t mfma_partial_bytes(int T, int d_model, int d_inter)
     return s > 1 ? align_up((size_t)s * T * d_model * sizeof(float), 256) : 0;
 }
 
-template <int NB>
+template <int NB, bool kRouted = false>
 static hipError_t launch_gate_up(const FwdArgs &a, const BranchTable &bt, int tiles_m)
 {
     long long tiles_n = 0;
@@ -544,14 +621,14 @@ static hipError_t launch_gate_up(const FwdArgs &a, const BranchTable &bt, int ti
     const long long grid = (long long)XCDS * ids_per_xcd(tiles_m * tiles_n);
     if (grid > 0x7fffffffLL) return note_hip_error("gate_up_mfma grid", hipErrorInvalidValue);
     ProfileScope ps(MLPMOE_KERNEL_GATE_UP_MFMA, a.stream);
-    gate_up_mfma<MFMA_WM, NB><<<(unsigned)grid, MFMA_WM * 128, 0, a.stream>>>(
+    gate_up_mfma<MFMA_WM, NB, kRouted><<<(unsigned)grid, MFMA_WM * 128, 0, a.stream>>>(
         static_cast<const uint16_t *>(a.x), static_cast<const uint16_t *>(a.Wg),
         static_cast<const uint16_t *>(a.Wu), static_cast<uint16_t *>(a.H), a.T, a.d_model, a.d_inter,
-        a.ldh, tiles_m, (int)tiles_n, bt);
+        a.ldh, tiles_m, (int)tiles_n, a.route, a.tile_need, bt);
     return launch_status("gate_up_mfma launch");
 }
 
-template <int NB>
+template <int NB, bool kRouted = false>
 static hipError_t launch_down(const FwdArgs &a, const BranchTable &bt, int tiles_m, int kt_total, int *splits_out)
 {
     const int tile_n = 64 * NB;
@@ -564,10 +641,37 @@ static hipError_t launch_down(const FwdArgs &a, const BranchTable &bt, int tiles
     if (grid > 0x7fffffffLL) return note_hip_error("down_mfma grid", hipErrorInvalidValue);
     *splits_out = splits;
     ProfileScope ps(MLPMOE_KERNEL_DOWN_MFMA, a.stream);
-    down_mfma<MFMA_WM, NB><<<(unsigned)grid, MFMA_WM * 128, 0, a.stream>>>(
+    down_mfma<MFMA_WM, NB, kRouted><<<(unsigned)grid, MFMA_WM * 128, 0, a.stream>>>(
         static_cast<const uint16_t *>(a.H), static_cast<const uint16_t *>(a.Wd), splits > 1 ? a.partial : a.out,
-        a.T, a.d_model, a.d_inter, a.ldh, tiles_m, tiles_n, splits, kt_total, bt);
+        a.T, a.d_model, a.d_inter, a.ldh, tiles_m, tiles_n, splits, kt_total, a.tile_need, bt);
     return launch_status("down_mfma launch");
+}
+
+// Fills a.tile_need from a.route (one byte per token tile and branch).
+hipError_t launch_route_tile_need(const FwdArgs &a, const BranchTable &bt)
+{
+    route_tile_need<<<ceil_div(a.T, BM), 256, 0, a.stream>>>(a.route, a.tile_need, a.T, bt.B);
+    return launch_status("route_tile_need launch");
+}
+
+// Per-token routing on the MFMA kernels (wide tiles; the shapes where narrow tiles pay are rare
+// once tiles are skipped).  a.tile_need must have been filled.
+hipError_t launch_mfma_routed_bf16(const FwdArgs &a, const BranchTable &bt)
+{
+    const int tiles_m = ceil_div(a.T, BM);
+    hipError_t e = launch_gate_up<4, true>(a, bt, tiles_m);
+    if (e != hipSuccess) return hipErrorLaunchFailure;
+    int splits = 1;
+    e = launch_down<4, true>(a, bt, tiles_m, k_tiles(bt), &splits);
+    if (e != hipSuccess) return hipErrorLaunchFailure;
+    if (splits > 1) {
+        ProfileScope ps(MLPMOE_KERNEL_SPLITK_REDUCE, a.stream);
+        const size_t n = (size_t)a.T * a.d_model;
+        size_t blocks = (n + 255) / 256;
+        if (blocks > 8192) blocks = 8192;
+        reduce_partials<<<(unsigned)blocks, 256, 0, a.stream>>>(a.partial, a.out, n, splits);
+    }
+    return launch_status("reduce_partials launch");
 }
 
 hipError_t launch_mfma_bf16(const FwdArgs &a, const BranchTable &bt)

@@ -95,9 +95,15 @@ size_t h_bytes(int T, int d_inter, int elem_bytes)
 
 // Dispatch with a ready branch table: path choice, workspace carving, launch.  No loops over
 // branches, no allocation, no synchronisation.
+size_t route_scratch_bytes(int T) { return align_up((size_t)ceil_div(T > 0 ? T : 1, 256) * MLPMOE_MAX_BRANCHES, 256); }
+
+// route: per-token routing [T, B] on the device, or nullptr.  Routed calls use the kernels that skip
+// (token tile, branch) pairs nobody is routed to when every branch boundary is a multiple of 8,
+// and the generic kernels (masking only) otherwise.
 int forward_table(const BranchTable &bt, bool aligned, const void *x, const void *Wg, const void *Wu,
                   const void *Wd, int T, int d_model, int d_inter, float *out, void *workspace,
-                  size_t workspace_bytes, int path, bool is_bf16, hipStream_t stream)
+                  size_t workspace_bytes, int path, bool is_bf16, hipStream_t stream,
+                  const uint8_t *route = nullptr)
 {
     // launch status is read back with hipGetLastError(): drop whatever an earlier, unrelated
     // runtime call of this thread left behind (e.g. a "not ready" from an event query)
@@ -107,6 +113,10 @@ int forward_table(const BranchTable &bt, bool aligned, const void *x, const void
     if (bt.n_runs == 0) {   // nothing active: the sum over branches is empty
         return launch_fill_zero(out, (size_t)T * d_model, stream) == hipSuccess ? MLPMOE_OK
                                                                                 : MLPMOE_ERR_HIP;
+    }
+    if (route) {
+        // the routed K loops start and stop at branch boundaries, not only at run boundaries
+        for (int b = 0; b <= bt.B && aligned; ++b) aligned = bt.off[b] % 8 == 0;
     }
     if (path == MLPMOE_PATH_AUTO)
         path = !aligned ? MLPMOE_PATH_GENERIC : (T <= 16 ? MLPMOE_PATH_DECODE : MLPMOE_PATH_MFMA);
@@ -123,16 +133,29 @@ int forward_table(const BranchTable &bt, bool aligned, const void *x, const void
     a.T = T; a.d_model = d_model; a.d_inter = d_inter;
     a.H = workspace;
     a.ldh = h_ld(d_inter);
-    a.partial_bytes = need - h_bytes(T, d_inter, elem);
+    a.partial_bytes = need - h_bytes(T, d_inter, elem) - route_scratch_bytes(T) - 256;
     a.partial = a.partial_bytes
                     ? reinterpret_cast<float *>(static_cast<char *>(workspace) + h_bytes(T, d_inter, elem))
                     : nullptr;
     a.stream = stream;
+    a.route = route;
+    a.tile_need = reinterpret_cast<uint8_t *>(static_cast<char *>(workspace) + need - route_scratch_bytes(T));
 
     hipError_t e;
-    if (path == MLPMOE_PATH_GENERIC) e = launch_generic(a, bt, is_bf16);
-    else if (path == MLPMOE_PATH_MFMA) e = launch_mfma_bf16(a, bt);
-    else e = launch_decode_bf16(a, bt);
+    if (path == MLPMOE_PATH_GENERIC) {
+        e = launch_generic(a, bt, is_bf16);
+    } else if (route) {
+        if (path == MLPMOE_PATH_MFMA) {
+            e = launch_route_tile_need(a, bt);
+            if (e == hipSuccess) e = launch_mfma_routed_bf16(a, bt);
+        } else {
+            e = launch_decode_routed_bf16(a, bt);
+        }
+    } else if (path == MLPMOE_PATH_MFMA) {
+        e = launch_mfma_bf16(a, bt);
+    } else {
+        e = launch_decode_bf16(a, bt);
+    }
     if (e != hipSuccess && g_err_detail[0] == 0) (void)note_hip_error("kernel launch", e);
     return e == hipSuccess ? MLPMOE_OK : MLPMOE_ERR_HIP;
 }
@@ -418,7 +441,7 @@ size_t mlpmoe_workspace_bytes(int T, int d_model, int d_inter, int B, int elem_b
     if (T == 0) return 256;
     size_t bytes = h_bytes(T, d_inter, elem_bytes);
     if (elem_bytes == 2) bytes += mfma_partial_bytes(T, d_model, d_inter);
-    return bytes + 256;
+    return bytes + 256 + route_scratch_bytes(T);     // slack, then the routed paths' tile table
 }
 
 int mlpmoe_forward_bf16_ws(const void *x, const void *W_gate, const void *W_up, const void *W_down,
@@ -464,6 +487,44 @@ int mlpmoe_forward_f32(const float *x, const float *W_gate, const float *W_up, c
 {
     return forward_owned(x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, T, d_model,
                          d_inter, B, out, false, static_cast<hipStream_t>(stream));
+}
+
+static int forward_routed(const void *x, const void *Wg, const void *Wu, const void *Wd, const int32_t *off,
+                          const float *alpha, const uint8_t *mask, const uint8_t *route, int T, int d_model,
+                          int d_inter, int B, float *out, void *workspace, size_t workspace_bytes, bool own,
+                          hipStream_t stream)
+{
+    int rc = validate_common(x, Wg, Wu, Wd, off, alpha, mask, T, d_model, d_inter, B, out);
+    if (rc != MLPMOE_OK) return rc;
+    if (T == 0) return MLPMOE_OK;
+    if (!route) return MLPMOE_ERR_NULL;
+    if (own) {
+        rc = owned_workspace(mlpmoe_workspace_bytes(T, d_model, d_inter, B, 2), &workspace, &workspace_bytes);
+        if (rc != MLPMOE_OK) return rc;
+    }
+    BranchTable bt;
+    build_table(off, alpha, mask, B, bt);
+    return forward_table(bt, fast_path_aligned(bt, d_model, d_inter), x, Wg, Wu, Wd, T, d_model, d_inter, out,
+                         workspace, workspace_bytes, MLPMOE_PATH_AUTO, true, stream, route);
+}
+
+int mlpmoe_forward_routed_bf16(const void *x, const void *W_gate, const void *W_up, const void *W_down,
+                               const int32_t *branch_offsets, const float *alpha, const uint8_t *active_mask,
+                               const uint8_t *route, int T, int d_model, int d_inter, int B, float *out,
+                               void *stream)
+{
+    return forward_routed(x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, route, T, d_model, d_inter,
+                          B, out, nullptr, 0, true, static_cast<hipStream_t>(stream));
+}
+
+int mlpmoe_forward_routed_bf16_ws(const void *x, const void *W_gate, const void *W_up, const void *W_down,
+                                  const int32_t *branch_offsets, const float *alpha,
+                                  const uint8_t *active_mask, const uint8_t *route, int T, int d_model,
+                                  int d_inter, int B, float *out, void *workspace, size_t workspace_bytes,
+                                  void *stream)
+{
+    return forward_routed(x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, route, T, d_model, d_inter,
+                          B, out, workspace, workspace_bytes, false, static_cast<hipStream_t>(stream));
 }
 
 struct mlpmoe_plan {

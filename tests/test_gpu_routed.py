@@ -1,0 +1,121 @@
+"""GPU parity for per-token routing over branches against the oracle (contract and exact modes)."""
+import numpy as np
+import pytest
+
+import oracle
+from gpu_util import BF16_TOL, to_dev, widen
+from paper_2511_21089_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def mm():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2511_21089_amd import binding
+    return binding
+
+
+def run_routed(mm, L, off, alpha, mask, route, T=None):
+    import torch
+    T = L.T if T is None else T
+    x, Wg, Wu, Wd = (to_dev(a) for a in (L.x[:T], L.W_gate, L.W_up, L.W_down))
+    r = torch.from_numpy(np.ascontiguousarray(route[:T])).cuda()
+    return mm.mlpmoe_forward_routed_bf16(x, Wg, Wu, Wd, off, alpha, mask, r).cpu().numpy()
+
+
+def check(got, L, off, alpha, mask, route, T=None, contract=True):
+    T = L.T if T is None else T
+    args = (widen(L.x[:T]), widen(L.W_gate), widen(L.W_up), widen(L.W_down), off, alpha, mask, route[:T])
+    assert np.all(np.isfinite(got))
+    e_e = oracle.rel_max_err(got, oracle.mlpmoe_forward_routed(*args, mode="exact"))
+    assert e_e <= BF16_TOL, ("exact", e_e)
+    if contract:
+        e_c = oracle.rel_max_err(got, oracle.mlpmoe_forward_routed(*args, mode="contract"))
+        assert e_c <= BF16_TOL, ("contract", e_c)
+
+
+def top_k_route(rng, T, B, k):
+    route = np.zeros((T, B), np.uint8)
+    for t in range(T):
+        route[t, rng.choice(B, size=k, replace=False)] = 1
+    return route
+
+
+def test_random_routing_prefill_and_decode(mm):
+    """B = 8 branches of 256 neurons, every token takes 5 random branches (>= 1000 neurons each)."""
+    L = synth.make_layer("qwen05b_pruned", 600, seed=51, d_model=256, d_inter=8 * 256)
+    off, _, mask, _ = mm.mlpmoe_slice(8 * 256, 8)
+    mask[L.inactive[:1]] = 0
+    alpha = L.alpha_draw
+    rng = np.random.default_rng(1)
+    route = top_k_route(rng, 600, 8, 5)
+    route[7] = 0                                        # a token that takes nothing
+    route[300:310] = 1                                  # tokens that take everything
+    got = run_routed(mm, L, off, alpha, mask, route)
+    check(got, L, off, alpha, mask, route)
+    assert np.all(got[7] == 0)
+    for T in (1, 5, 16):                                # decode kernels
+        check(run_routed(mm, L, off, alpha, mask, route, T), L, off, alpha, mask, route, T, contract=(T > 1))
+
+
+def test_grouped_routing_skips_pairs_nobody_takes(mm):
+    """Tokens sorted by route: whole (256-token tile, branch) pairs are skipped; results unchanged.
+    H is poisoned first: skipped pairs must never be read."""
+    import torch
+    L = synth.make_layer("qwen05b", 1024, seed=52, d_model=256, d_inter=8 * 256)
+    off, alpha, mask, _ = mm.mlpmoe_slice(8 * 256, 8)
+    alpha = L.alpha_draw
+    route = np.zeros((1024, 8), np.uint8)
+    for g in range(4):                                  # token tile g takes branches g .. g+4
+        route[g * 256:(g + 1) * 256, g:g + 5] = 1
+    x, Wg, Wu, Wd = (to_dev(a) for a in (L.x, L.W_gate, L.W_up, L.W_down))
+    ws = mm.new_workspace(1024, 256, 8 * 256, 8)
+    ws.view(torch.int16).fill_(0x7FC0)                  # bf16 NaN everywhere in the workspace
+    r = torch.from_numpy(route).cuda()
+    got = mm.mlpmoe_forward_routed_bf16(x, Wg, Wu, Wd, off, alpha, mask, r, workspace=ws).cpu().numpy()
+    check(got, L, off, alpha, mask, route)
+    # all ones == the unrouted forward, bit for bit
+    ones = torch.ones((1024, 8), dtype=torch.uint8, device="cuda")
+    a = mm.mlpmoe_forward_routed_bf16(x, Wg, Wu, Wd, off, alpha, mask, ones)
+    b = mm.mlpmoe_forward_bf16(x, Wg, Wu, Wd, off, alpha, mask)
+    assert torch.equal(a, b)
+    # decode: branches no token takes are never read (NaN weights there must not leak)
+    Wg2, Wu2, Wd2 = L.W_gate.copy(), L.W_up.copy(), L.W_down.copy()
+    Wg2[5 * 256:] = 0x7FC0
+    Wd2[:, 5 * 256:] = 0x7FC0
+    r16 = route[:16]                                    # tokens of group 0: branches 0..4 only
+    got = mm.mlpmoe_forward_routed_bf16(x[:16], to_dev(Wg2), Wu, to_dev(Wd2), off, alpha, mask,
+                                        torch.from_numpy(r16).cuda()).cpu().numpy()
+    check(got, L, off, alpha, mask, route, 16)
+    # ... and in prefill, tile 0 (branches 0..4) stays finite while later tiles do see the NaNs
+    got = mm.mlpmoe_forward_routed_bf16(x, to_dev(Wg2), Wu, to_dev(Wd2), off, alpha, mask, r).cpu().numpy()
+    assert np.all(np.isfinite(got[:256])) and not np.all(np.isfinite(got[256:]))
+
+
+def test_unaligned_table_takes_the_generic_kernels(mm):
+    L = synth.make_layer("qwen05b", 70, seed=53, d_model=72, d_inter=1403)
+    off = np.array([0, 337, 337, 501, 950, 1403], np.int32)
+    mask = np.array([1, 1, 0, 1, 1], np.uint8)
+    alpha = np.random.default_rng(3).uniform(0.9, 1.2, size=5).astype(np.float32)
+    route = top_k_route(np.random.default_rng(4), 70, 5, 4)
+    check(run_routed(mm, L, off, alpha, mask, route), L, off, alpha, mask, route, contract=False)
+
+
+def test_routed_full_size_sampled(mm):
+    """8B-shaped layer, T = 4096, tokens grouped so that each tile of 256 takes 4 of 16 branches."""
+    import torch
+    L = synth.make_layer("llama8b", 4096, seed=54)
+    off, _, mask, _ = mm.mlpmoe_slice(14336, 16)
+    alpha = L.alpha_draw
+    route = np.zeros((4096, 16), np.uint8)
+    for g in range(16):
+        for j in range(4):
+            route[g * 256:(g + 1) * 256, (g + 3 * j) % 16] = 1
+    x, Wg, Wu, Wd = (to_dev(a) for a in (L.x, L.W_gate, L.W_up, L.W_down))
+    got = mm.mlpmoe_forward_routed_bf16(x, Wg, Wu, Wd, off, alpha, mask, torch.from_numpy(route).cuda()).cpu().numpy()
+    rows = np.random.default_rng(6).choice(4096, size=12, replace=False)
+    ref = oracle.mlpmoe_forward_routed(widen(L.x[rows]), widen(L.W_gate), widen(L.W_up), widen(L.W_down), off, alpha,
+                                       mask, route[rows], mode="contract")
+    assert oracle.rel_max_err(got[rows], ref) <= BF16_TOL

@@ -263,7 +263,8 @@ enum {
     MLPMOE_KERNEL_DECODE_DOWN = 5,
     MLPMOE_KERNEL_GATE_UP_GENERIC = 6,
     MLPMOE_KERNEL_DOWN_GENERIC = 7,
-    MLPMOE_KERNEL_FILL_ZERO = 8
+    MLPMOE_KERNEL_FILL_ZERO = 8,
+    MLPMOE_KERNEL_ROUTE_TILES = 9
 };
 MLPMOE_API int mlpmoe_profile_enable(int capacity);
 MLPMOE_API int mlpmoe_profile_collect(int *ids, float *ms, int capacity);

@@ -303,7 +303,8 @@ class Plan:
 
 
 KERNEL_NAMES = {1: "gate_up_mfma", 2: "down_mfma", 3: "splitk_reduce", 4: "decode_gate_up",
-                5: "decode_down", 6: "gate_up_generic", 7: "down_generic", 8: "fill_zero"}
+                5: "decode_down", 6: "gate_up_generic", 7: "down_generic", 8: "fill_zero",
+                9: "route_tiles"}
 
 
 def mlpmoe_profile_enable(capacity: int):

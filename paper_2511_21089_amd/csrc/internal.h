@@ -35,7 +35,7 @@ struct FwdArgs {
     float *partial;     // split-K partial sums, or nullptr
     size_t partial_bytes;
     const uint8_t *route = nullptr;   // per-token routing [T, B] (device), or nullptr
-    uint8_t *tile_need = nullptr;     // [ceil(T / 256), B] scratch of the routed paths (device)
+    uint8_t *route_scratch = nullptr; // route_scratch_bytes(T, d_inter) bytes for the routed MFMA path (device)
     hipStream_t stream;
 };
 
@@ -70,7 +70,7 @@ size_t mfma_partial_bytes(int T, int d_model, int d_inter);
 hipError_t launch_fill_zero(float *out, size_t n, hipStream_t s);
 hipError_t launch_generic(const FwdArgs &a, const BranchTable &bt, bool is_bf16);
 hipError_t launch_mfma_bf16(const FwdArgs &a, const BranchTable &bt);
-hipError_t launch_route_tile_need(const FwdArgs &a, const BranchTable &bt);
+size_t route_scratch_bytes(int T, int d_inter);
 hipError_t launch_mfma_routed_bf16(const FwdArgs &a, const BranchTable &bt);
 hipError_t launch_decode_bf16(const FwdArgs &a, const BranchTable &bt);
 hipError_t launch_decode_routed_bf16(const FwdArgs &a, const BranchTable &bt);

@@ -441,7 +441,7 @@ static hipError_t launch_decode_impl(const FwdArgs &a, const BranchTable &bt)
 
 hipError_t launch_decode_bf16(const FwdArgs &a, const BranchTable &bt) { return launch_decode_impl<false>(a, bt); }
 
-// Per-token routing, T <= 16: the kernels read a.route themselves; a.tile_need is not used.
+// Per-token routing, T <= 16: the kernels read a.route themselves and need no scratch.
 hipError_t launch_decode_routed_bf16(const FwdArgs &a, const BranchTable &bt) { return launch_decode_impl<true>(a, bt); }
 
 }  // namespace mlpmoe

@@ -395,22 +395,57 @@ __device__ __forceinline__ bool tile_of(int id, int tiles_m, int tiles_n, int &t
     return true;
 }
 
+// Scratch of the routed kernels, filled by route_tile_list from route[T, B]:
+//   tile_need[tm * B + b]  != 0 if some token of token tile tm (256 tokens) is routed to branch b;
+//   counts[g], list[g * stride + i]: the live gate+up tiles of token-tile group g (GROUP_M token
+//   tiles) in the order the kernel walks them: by N tile, then by token tile.  An entry is
+//   tn * gsz + (tm - g * GROUP_M), gsz = token tiles in the group.  A tile is live if some token of
+//   its token tile is routed to an active branch that owns one of its neurons.
+struct RouteTiles {
+    const uint8_t *tile_need;
+    const uint32_t *counts;
+    const uint32_t *list;
+    int stride;
+};
+
 // grid.x = 8 * ids_per_xcd(tilesM * sum over runs of N tiles).
-// kRouted: per-token routing.  route[t * B + b] != 0 says token t takes branch b; tile_need[tm * B + b]
-// != 0 says some token of token tile tm does.  A tile none of whose branches is needed is skipped
-// (the down projection skips the same (token tile, branch) pairs), and H is multiplied by the
-// token's route bit, so that it is exactly 0 where a token does not take a branch.
+// kRouted: per-token routing.  route[t * B + b] != 0 says token t takes branch b.  Only the live
+// tiles are computed: workgroup ids are dealt over the compacted tile list as tile_of() deals them
+// over the full grid (one contiguous stretch of the list per XCD), the ids left over exit.  The
+// down projection skips the same (token tile, branch) pairs, and H is multiplied by the token's
+// route bit, so that it is exactly 0 where a token does not take a branch.
 template <int WM, int NB, bool kRouted>
 __global__ void __launch_bounds__(WM * 128)
 gate_up_mfma(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
              const uint16_t *__restrict__ Wu, uint16_t *__restrict__ H, int T, int d_model, int d_inter,
-             int ldh, int tiles_m, int tiles_n, const uint8_t *__restrict__ route,
-             const uint8_t *__restrict__ tile_need, BranchTable bt)
+             int ldh, int tiles_m, int tiles_n, const uint8_t *__restrict__ route, RouteTiles rt,
+             BranchTable bt)
 {
     __shared__ __attribute__((aligned(1024))) char lds[LDS_BYTES];
     constexpr int BNH = 32 * NB;                  // neurons per tile
     int tm, tn;
-    if (!tile_of(blockIdx.x, tiles_m, tiles_n, tm, tn)) return;
+    if (kRouted) {
+        const int groups = (tiles_m + GROUP_M - 1) / GROUP_M;
+        int total = 0;
+        for (int g = 0; g < groups; ++g) total += (int)rt.counts[g];
+        const int per_xcd = ids_per_xcd(total);
+        const int k = blockIdx.x / XCDS;
+        const int logical = (blockIdx.x % XCDS) * per_xcd + k;
+        if (k >= per_xcd || logical >= total) return;
+        int g = 0, before = 0;
+        for (; g < groups - 1; ++g) {
+            const int c = (int)rt.counts[g];
+            if (logical < before + c) break;
+            before += c;
+        }
+        const int e = (int)rt.list[(size_t)g * rt.stride + (logical - before)];
+        const int m0 = g * GROUP_M;
+        const int gsz = tiles_m - m0 < GROUP_M ? tiles_m - m0 : GROUP_M;
+        tm = m0 + e % gsz;
+        tn = e / gsz;
+    } else if (!tile_of(blockIdx.x, tiles_m, tiles_n, tm, tn)) {
+        return;
+    }
     int n0 = 0, n_end = 0;
     for (int r = 0; r < bt.n_runs; ++r) {
         const int n = (bt.run_end[r] - bt.run_start[r] + BNH - 1) / BNH;
@@ -423,13 +458,6 @@ gate_up_mfma(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
     }
     if (n_end == 0) return;
     const int t0 = tm * BM;
-    if (kRouted) {
-        const int n1 = n0 + BNH < n_end ? n0 + BNH : n_end;
-        bool any = false;
-        for (int b = branch_of(bt, n0); b < bt.B && bt.off[b] < n1; ++b)
-            any = any || (((bt.active >> b) & 1ULL) && tile_need[tm * bt.B + b]);
-        if (!any) return;
-    }
 
     constexpr int MI = 16 / WM;
     f32x4 accg[MI][NB], accu[MI][NB];
@@ -550,16 +578,136 @@ down_mfma(const uint16_t *__restrict__ H, const uint16_t *__restrict__ Wd, float
     }
 }
 
-// tile_need[tm * B + b] = 1 if some token of token tile tm (256 tokens) is routed to branch b.
-__global__ void __launch_bounds__(256)
-route_tile_need(const uint8_t *__restrict__ route, uint8_t *__restrict__ tile_need, int T, int B)
+constexpr int ROUTE_MAX_TILES_N = 32768;           // N tiles of the gate+up projection the tile list handles
+
+// Fills the routed kernels' scratch (see RouteTiles) for one group of GROUP_M token tiles per
+// workgroup.  BNH = neurons per gate+up tile; tiles_n = N tiles over the runs of active branches.
+template <int BNH>
+__global__ void __launch_bounds__(1024)
+route_tile_list(const uint8_t *__restrict__ route, uint8_t *__restrict__ tile_need, uint32_t *__restrict__ counts,
+                uint32_t *__restrict__ list, int stride, int T, int tiles_m, int tiles_n, BranchTable bt)
 {
-    const int t = blockIdx.x * BM + threadIdx.x;
-    for (int b = 0; b < B; ++b) {
-        const int mine = t < T ? route[(size_t)t * B + b] != 0 : 0;
-        const int any = __syncthreads_or(mine);
-        if (threadIdx.x == 0) tile_need[blockIdx.x * B + b] = (uint8_t)(any != 0);
+    __shared__ uint8_t need[GROUP_M][MLPMOE_MAX_BRANCHES];
+    __shared__ uint8_t live[ROUTE_MAX_TILES_N];
+    __shared__ int s_off[MLPMOE_MAX_BRANCHES + 1], s_run_start[MLPMOE_MAX_BRANCHES], s_run_end[MLPMOE_MAX_BRANCHES];
+    __shared__ int wave_sum[16];
+    const int B = bt.B;
+    const int g = blockIdx.x, m0 = g * GROUP_M;
+    const int gsz = tiles_m - m0 < GROUP_M ? tiles_m - m0 : GROUP_M;
+    for (int i = threadIdx.x; i < GROUP_M * MLPMOE_MAX_BRANCHES; i += 1024) (&need[0][0])[i] = 0;
+    if (threadIdx.x < 64) {
+        // branch table -> LDS: constant indices keep the reads of the kernel arguments scalar
+        const int l = threadIdx.x;
+        int v_off = 0, v_start = 0, v_end = 0;
+#pragma unroll
+        for (int i = 0; i < MLPMOE_MAX_BRANCHES; ++i) v_off = l == i ? bt.off[i] : v_off;
+#pragma unroll
+        for (int i = 0; i < kMaxRuns; ++i) {
+            v_start = l == i ? bt.run_start[i] : v_start;
+            v_end = l == i ? bt.run_end[i] : v_end;
+        }
+        s_off[l] = v_off;
+        s_run_start[l] = v_start;
+        s_run_end[l] = v_end;
+        if (l == 0) s_off[MLPMOE_MAX_BRANCHES] = bt.off[MLPMOE_MAX_BRANCHES];
     }
+    __syncthreads();
+    // the group's rows of route are one contiguous stretch of bytes.  Flags already set are not
+    // stored again: the LDS serialises the lanes of a store to one address, reads are broadcast
+    const size_t base = (size_t)m0 * BM * B;
+    const long long t_end = (long long)(m0 + gsz) * BM < T ? (long long)(m0 + gsz) * BM : T;
+    const int n_bytes = (int)((t_end - (long long)m0 * BM) * B);
+    const uint8_t *rg = route + base;
+    // 16 bytes at a time where the pointer allows it, several loads in flight per thread; one
+    // division per 16 bytes, the (token, branch) of the following bytes by stepping
+    const int n_vec = (reinterpret_cast<uintptr_t>(rg) & 15u) == 0 ? n_bytes / 16 : 0;
+    for (int c0 = threadIdx.x; c0 < n_vec; c0 += 4 * 1024) {
+        u32x4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int c = c0 + u * 1024;
+            v[u] = c < n_vec ? *reinterpret_cast<const u32x4 *>(rg + (size_t)c * 16) : u32x4{0, 0, 0, 0};
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if ((v[u][0] | v[u][1] | v[u][2] | v[u][3]) == 0) continue;
+            const int i = (c0 + u * 1024) * 16;
+            int t = i / B, b = i - t * B;
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                if (((v[u][k / 4] >> (8 * (k % 4))) & 0xffu) && !need[t / BM][b]) need[t / BM][b] = 1;
+                if (++b == B) {
+                    b = 0;
+                    ++t;
+                }
+            }
+        }
+    }
+    for (int i0 = n_vec * 16 + threadIdx.x; i0 < n_bytes; i0 += 8 * 1024) {
+        uint8_t v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int i = i0 + u * 1024;
+            v[u] = i < n_bytes ? rg[i] : (uint8_t)0;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (v[u]) {
+                const int i = i0 + u * 1024;
+                if (!need[(i / B) / BM][i % B]) need[(i / B) / BM][i % B] = 1;
+            }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < gsz * B; i += 1024) tile_need[(size_t)m0 * B + i] = need[i / B][i % B];
+
+    // live[tn]: bit j says tile (m0 + j, tn) is live; one thread per N tile.  The branch table was
+    // copied to LDS above, so that the walks over runs and branches are chains of LDS reads.
+    for (int tn = threadIdx.x; tn < tiles_n; tn += 1024) {
+        int n0 = 0, n1 = 0, left = tn;
+        bool found = false;
+        for (int r = 0; r < bt.n_runs; ++r) {
+            const int n = (s_run_end[r] - s_run_start[r] + BNH - 1) / BNH;
+            if (!found && left < n) {
+                n0 = s_run_start[r] + left * BNH;
+                n1 = n0 + BNH < s_run_end[r] ? n0 + BNH : s_run_end[r];
+                found = true;
+            }
+            left -= n;
+        }
+        unsigned bits = 0;
+        for (int b = 0; b < B; ++b) {
+            const int lo = s_off[b], hi = s_off[b + 1];
+            if (!((bt.active >> b) & 1ULL) || hi <= lo || hi <= n0 || lo >= n1) continue;   // owns no neuron of the tile
+            for (int j = 0; j < GROUP_M; ++j) bits |= need[j][b] ? 1u << j : 0u;
+        }
+        live[tn] = (uint8_t)bits;
+    }
+    __syncthreads();
+
+    // compaction in list order (by N tile, then token tile): every thread takes a contiguous stretch
+    // of N tiles, an exclusive prefix over the threads gives its first position
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int per = (tiles_n + 1023) / 1024;
+    const int tn0 = threadIdx.x * per;
+    const int tn1 = tn0 + per < tiles_n ? tn0 + per : tiles_n;
+    int mine = 0;
+    for (int tn = tn0; tn < tn1; ++tn) mine += __popc((unsigned)live[tn]);
+    int incl = mine;
+    for (int d = 1; d < 64; d <<= 1) {
+        const int v = __shfl_up(incl, d);
+        incl += lane >= d ? v : 0;
+    }
+    if (lane == 63) wave_sum[wave] = incl;
+    __syncthreads();
+    int pos = incl - mine, total = 0;
+    for (int w = 0; w < 16; ++w) {
+        pos += w < wave ? wave_sum[w] : 0;
+        total += wave_sum[w];
+    }
+    if (threadIdx.x == 0) counts[g] = (uint32_t)total;
+    for (int tn = tn0; tn < tn1; ++tn)
+        for (int j = 0; j < gsz; ++j)
+            if ((live[tn] >> j) & 1) list[(size_t)g * stride + pos++] = (uint32_t)(tn * gsz + j);
 }
 
 // out[i] = sum_z partial[z][i], summed in z order: deterministic.
@@ -606,6 +754,24 @@ bool narrow_tiles_pay(long long wide_tiles)
 
 int mfma_down_splits(int T, int d_model, int k_elems) { return down_splits(T, d_model, k_elems, 2 * BNH_MAX); }
 
+// Layout of the routed kernels' scratch block (256-byte aligned): tile_need, counts, list.
+// The list holds, per group of GROUP_M token tiles, up to GROUP_M * (N tiles) entries; the N tiles
+// over runs of active branches number at most d_inter / 128 + one per run.
+namespace {
+int route_list_stride(int d_inter) { return GROUP_M * (d_inter / BNH_MAX + MLPMOE_MAX_BRANCHES + 1); }
+size_t route_need_bytes(int T) { return align_up((size_t)ceil_div(T, BM) * MLPMOE_MAX_BRANCHES, 256); }
+size_t route_counts_bytes(int T) { return align_up((size_t)ceil_div(ceil_div(T, BM), GROUP_M) * sizeof(uint32_t), 256); }
+}  // namespace
+
+size_t route_scratch_bytes(int T, int d_inter)
+{
+    if (T < 1) T = 1;
+    if (d_inter < 0) d_inter = 0;
+    const size_t groups = (size_t)ceil_div(ceil_div(T, BM), GROUP_M);
+    return route_need_bytes(T) + route_counts_bytes(T) +
+           align_up(groups * route_list_stride(d_inter) * sizeof(uint32_t), 256);
+}
+
 size_t mfma_partial_bytes(int T, int d_model, int d_inter)
 {
     // sized for the wide tiles: narrow tiles double the tile count and so never split more
@@ -620,11 +786,29 @@ static hipError_t launch_gate_up(const FwdArgs &a, const BranchTable &bt, int ti
     for (int r = 0; r < bt.n_runs; ++r) tiles_n += ceil_div(bt.run_end[r] - bt.run_start[r], 32 * NB);
     const long long grid = (long long)XCDS * ids_per_xcd(tiles_m * tiles_n);
     if (grid > 0x7fffffffLL) return note_hip_error("gate_up_mfma grid", hipErrorInvalidValue);
+    RouteTiles rt{nullptr, nullptr, nullptr, 0};
+    if (kRouted) {
+        // one launch builds the tile list (and tile_need, which the down projection reads as well)
+        static_assert(!kRouted || 32 * NB == BNH_MAX, "the list's row stride is sized for wide tiles");
+        uint8_t *need = a.route_scratch;
+        uint32_t *counts = reinterpret_cast<uint32_t *>(a.route_scratch + route_need_bytes(a.T));
+        uint32_t *list = reinterpret_cast<uint32_t *>(a.route_scratch + route_need_bytes(a.T) + route_counts_bytes(a.T));
+        const int stride = route_list_stride(a.d_inter);
+        if ((long long)GROUP_M * tiles_n > stride || tiles_n > ROUTE_MAX_TILES_N)
+            return note_hip_error("route tile list size", hipErrorInvalidValue);
+        {
+            ProfileScope ps(MLPMOE_KERNEL_ROUTE_TILES, a.stream);
+            route_tile_list<32 * NB><<<ceil_div(tiles_m, GROUP_M), 1024, 0, a.stream>>>(
+                a.route, need, counts, list, stride, a.T, tiles_m, (int)tiles_n, bt);
+        }
+        if (launch_status("route_tile_list launch") != hipSuccess) return hipErrorLaunchFailure;
+        rt = RouteTiles{need, counts, list, stride};
+    }
     ProfileScope ps(MLPMOE_KERNEL_GATE_UP_MFMA, a.stream);
     gate_up_mfma<MFMA_WM, NB, kRouted><<<(unsigned)grid, MFMA_WM * 128, 0, a.stream>>>(
         static_cast<const uint16_t *>(a.x), static_cast<const uint16_t *>(a.Wg),
         static_cast<const uint16_t *>(a.Wu), static_cast<uint16_t *>(a.H), a.T, a.d_model, a.d_inter,
-        a.ldh, tiles_m, (int)tiles_n, a.route, a.tile_need, bt);
+        a.ldh, tiles_m, (int)tiles_n, a.route, rt, bt);
     return launch_status("gate_up_mfma launch");
 }
 
@@ -643,19 +827,12 @@ static hipError_t launch_down(const FwdArgs &a, const BranchTable &bt, int tiles
     ProfileScope ps(MLPMOE_KERNEL_DOWN_MFMA, a.stream);
     down_mfma<MFMA_WM, NB, kRouted><<<(unsigned)grid, MFMA_WM * 128, 0, a.stream>>>(
         static_cast<const uint16_t *>(a.H), static_cast<const uint16_t *>(a.Wd), splits > 1 ? a.partial : a.out,
-        a.T, a.d_model, a.d_inter, a.ldh, tiles_m, tiles_n, splits, kt_total, a.tile_need, bt);
+        a.T, a.d_model, a.d_inter, a.ldh, tiles_m, tiles_n, splits, kt_total, a.route_scratch, bt);
     return launch_status("down_mfma launch");
 }
 
-// Fills a.tile_need from a.route (one byte per token tile and branch).
-hipError_t launch_route_tile_need(const FwdArgs &a, const BranchTable &bt)
-{
-    route_tile_need<<<ceil_div(a.T, BM), 256, 0, a.stream>>>(a.route, a.tile_need, a.T, bt.B);
-    return launch_status("route_tile_need launch");
-}
-
-// Per-token routing on the MFMA kernels (wide tiles; the shapes where narrow tiles pay are rare
-// once tiles are skipped).  a.tile_need must have been filled.
+// Per-token routing on the MFMA kernels (wide tiles: how many tiles are live is known only on the
+// device).  a.route_scratch is route_scratch_bytes(T, d_inter) bytes, 256-byte aligned.
 hipError_t launch_mfma_routed_bf16(const FwdArgs &a, const BranchTable &bt)
 {
     const int tiles_m = ceil_div(a.T, BM);

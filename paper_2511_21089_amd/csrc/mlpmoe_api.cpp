@@ -95,8 +95,6 @@ size_t h_bytes(int T, int d_inter, int elem_bytes)
 
 // Dispatch with a ready branch table: path choice, workspace carving, launch.  No loops over
 // branches, no allocation, no synchronisation.
-size_t route_scratch_bytes(int T) { return align_up((size_t)ceil_div(T > 0 ? T : 1, 256) * MLPMOE_MAX_BRANCHES, 256); }
-
 // route: per-token routing [T, B] on the device, or nullptr.  Routed calls use the kernels that skip
 // (token tile, branch) pairs nobody is routed to when every branch boundary is a multiple of 8,
 // and the generic kernels (masking only) otherwise.
@@ -133,24 +131,19 @@ int forward_table(const BranchTable &bt, bool aligned, const void *x, const void
     a.T = T; a.d_model = d_model; a.d_inter = d_inter;
     a.H = workspace;
     a.ldh = h_ld(d_inter);
-    a.partial_bytes = need - h_bytes(T, d_inter, elem) - route_scratch_bytes(T) - 256;
+    a.partial_bytes = need - h_bytes(T, d_inter, elem) - route_scratch_bytes(T, d_inter) - 256;
     a.partial = a.partial_bytes
                     ? reinterpret_cast<float *>(static_cast<char *>(workspace) + h_bytes(T, d_inter, elem))
                     : nullptr;
     a.stream = stream;
     a.route = route;
-    a.tile_need = reinterpret_cast<uint8_t *>(static_cast<char *>(workspace) + need - route_scratch_bytes(T));
+    a.route_scratch = reinterpret_cast<uint8_t *>(static_cast<char *>(workspace) + need - route_scratch_bytes(T, d_inter));
 
     hipError_t e;
     if (path == MLPMOE_PATH_GENERIC) {
         e = launch_generic(a, bt, is_bf16);
     } else if (route) {
-        if (path == MLPMOE_PATH_MFMA) {
-            e = launch_route_tile_need(a, bt);
-            if (e == hipSuccess) e = launch_mfma_routed_bf16(a, bt);
-        } else {
-            e = launch_decode_routed_bf16(a, bt);
-        }
+        e = path == MLPMOE_PATH_MFMA ? launch_mfma_routed_bf16(a, bt) : launch_decode_routed_bf16(a, bt);
     } else if (path == MLPMOE_PATH_MFMA) {
         e = launch_mfma_bf16(a, bt);
     } else {
@@ -441,7 +434,7 @@ size_t mlpmoe_workspace_bytes(int T, int d_model, int d_inter, int B, int elem_b
     if (T == 0) return 256;
     size_t bytes = h_bytes(T, d_inter, elem_bytes);
     if (elem_bytes == 2) bytes += mfma_partial_bytes(T, d_model, d_inter);
-    return bytes + 256 + route_scratch_bytes(T);     // slack, then the routed paths' tile table
+    return bytes + 256 + route_scratch_bytes(T, d_inter);     // slack, then the routed path's tile tables
 }
 
 int mlpmoe_forward_bf16_ws(const void *x, const void *W_gate, const void *W_up, const void *W_down,

@@ -25,12 +25,13 @@ def run_routed(mm, L, off, alpha, mask, route, T=None):
     return mm.mlpmoe_forward_routed_bf16(x, Wg, Wu, Wd, off, alpha, mask, r).cpu().numpy()
 
 
-def check(got, L, off, alpha, mask, route, T=None, contract=True):
+def check(got, L, off, alpha, mask, route, T=None, contract=True, exact=True):
     T = L.T if T is None else T
     args = (widen(L.x[:T]), widen(L.W_gate), widen(L.W_up), widen(L.W_down), off, alpha, mask, route[:T])
     assert np.all(np.isfinite(got))
-    e_e = oracle.rel_max_err(got, oracle.mlpmoe_forward_routed(*args, mode="exact"))
-    assert e_e <= BF16_TOL, ("exact", e_e)
+    if exact:
+        e_e = oracle.rel_max_err(got, oracle.mlpmoe_forward_routed(*args, mode="exact"))
+        assert e_e <= BF16_TOL, ("exact", e_e)
     if contract:
         e_c = oracle.rel_max_err(got, oracle.mlpmoe_forward_routed(*args, mode="contract"))
         assert e_c <= BF16_TOL, ("contract", e_c)
@@ -119,3 +120,38 @@ def test_routed_full_size_sampled(mm):
     ref = oracle.mlpmoe_forward_routed(widen(L.x[rows]), widen(L.W_gate), widen(L.W_up), widen(L.W_down), off, alpha,
                                        mask, route[rows], mode="contract")
     assert oracle.rel_max_err(got[rows], ref) <= BF16_TOL
+
+
+def test_tile_list_ragged_groups_uneven_branches_unaligned_route(mm):
+    """Ten token tiles (two groups of the tile list, the second with 2 tiles, the last tile ragged),
+    twelve branches of unequal width (N tiles that span two branches, an empty and an inactive
+    branch), a route array that starts at an odd address, and token tiles that take only some
+    branches, so that the compacted tile list has holes everywhere.  Compared in contract mode only:
+    a third of the rows are exactly 0 and many tokens take a few neurons, which drags the rms of the
+    whole output far below the large elements, and the contract oracle itself then sits 2e-2 of
+    that rms away from the exact one (the single bf16 rounding of H, 0.3 % of the element)."""
+    import torch
+    widths = [40, 200, 136, 72, 264, 8, 0, 120, 304, 96, 160, 200]
+    off = np.concatenate([[0], np.cumsum(widths)]).astype(np.int32)
+    B, d_inter, d_model, T = 12, int(off[-1]), 128, 9 * 256 + 77
+    L = synth.make_layer("qwen05b", T, seed=55, d_model=d_model, d_inter=d_inter)
+    rng = np.random.default_rng(8)
+    alpha = rng.uniform(0.8, 1.3, size=B).astype(np.float32)
+    mask = np.ones(B, np.uint8)
+    mask[8] = 0
+    route = np.zeros((T, B), np.uint8)
+    for tm in range(10):
+        allowed = rng.choice(B, size=int(rng.integers(1, 6)), replace=False)
+        sl = slice(tm * 256, min(T, (tm + 1) * 256))
+        n = sl.stop - sl.start
+        route[sl][:, allowed] = rng.integers(0, 2, size=(n, len(allowed)), dtype=np.uint8)
+    route[5 * 256:6 * 256] = 0                           # a token tile that takes nothing at all
+    x, Wg, Wu, Wd = (to_dev(a) for a in (L.x, L.W_gate, L.W_up, L.W_down))
+    for shift in (0, 3):
+        buf = torch.zeros(T * B + 16, dtype=torch.uint8, device="cuda")
+        r = buf[shift:shift + T * B].view(T, B)
+        r.copy_(torch.from_numpy(route))
+        assert r.data_ptr() % 16 == shift
+        got = mm.mlpmoe_forward_routed_bf16(x, Wg, Wu, Wd, off, alpha, mask, r).cpu().numpy()
+        check(got, L, off, alpha, mask, route, exact=False)
+        assert np.all(got[5 * 256:6 * 256] == 0)

@@ -35,11 +35,11 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 # and reported as null when the source has changed since.
 TRAFFIC = {
     # (workload, kernel): (sha256 of the kernel's source file, bytes per launch = read + written)
-    # gate_up_mfma at T=4096: 1409.4 MB read (x is re-read once per group of 4 neuron tiles and the
+    # gate_up_mfma at T=4096: 1409.5 MB read (x is re-read once per group of 4 neuron tiles and the
     # weights once per XCD that needs them: 5.3x the 268 MB the kernel has to read) + 117.6 MB written
-    ("llama8b_T4096", "gate_up_mfma"): ("fafdf3ef106ddec835f655c46c50d8118a5a6f86a2f344d980193dd2cf8a0492", 1527.1e6),
-    # decode gate+up at T=1: 235.1 MB read (the weights, once) + 0.1 MB written
-    ("llama8b_T1", "decode_gate_up"): ("aec3657d19c1dc0841a3da88da2e8f367a683bc41f3f5d0cef39f22d7fe294c4", 235.2e6),
+    ("llama8b_T4096", "gate_up_mfma"): ("36b1ae1914e4c8ab3caf7375324f31112be6c9cadf6c0043df9384c0aa168176", 1527.1e6),
+    # decode gate+up at T=1: 236.1 MB read (the weights, once) + 0.1 MB written
+    ("llama8b_T1", "decode_gate_up"): ("b1d57b605eff02852f3ec4c5de5509d3e0c4d4cc5d2d5166b9d0cabd5a5dfcf9", 236.2e6),
 }
 KERNEL_SOURCE = {"gate_up_mfma": "kernels_mfma.hip", "down_mfma": "kernels_mfma.hip",
                  "decode_gate_up": "kernels_decode.hip", "decode_down": "kernels_decode.hip"}

@@ -151,3 +151,22 @@ def rel_max_err(got, ref) -> float:
     if rms == 0.0:
         return 0.0 if num == 0.0 else float("inf")
     return num / rms
+
+
+def round_to_bf16(a):
+    """Values of `a` rounded to the nearest bfloat16 (ties to even), returned as float64.
+
+    From the format's definition (1 sign, 8 exponent, 7 fraction bits, the exponent range of
+    binary32): a normal magnitude m * 2^e with m in [0.5, 1) keeps 8 significant bits, i.e. it is
+    rint(m * 256) / 256 * 2^e; below 2^-126 the spacing is the fixed 2^-133; magnitudes that round to
+    2^128 or more become infinite.  numpy's rint rounds halves to even.  Used for the forward whose
+    result is stored as bf16: the sum of Sec. 3.1 rounded once."""
+    a = np.asarray(a, dtype=np.float64)
+    mag = np.abs(a)
+    m, e = np.frexp(mag)
+    normal = np.ldexp(np.rint(m * 256.0) / 256.0, e)
+    sub = np.rint(mag / 2.0 ** -133) * 2.0 ** -133
+    r = np.where(mag < 2.0 ** -126, sub, normal)
+    r = np.where(r >= 2.0 ** 128, np.inf, r)
+    r = np.where(np.isfinite(mag), r, mag)          # inf and nan pass through
+    return np.copysign(r, a)

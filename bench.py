@@ -224,6 +224,19 @@ def others(mm, synth, torch, seed):
                     row["T%d_us" % T] = round(ms * 1e3, 2)
                 sweep["K%d" % K] = row
             res["llama8b_first_k_sweep"] = sweep
+            # the same forward with the result stored as bf16 (T = 4096 and T = 1)
+            o16 = {}
+            for T in (4096, 1):
+                xT = xs[:T].contiguous()
+                out = torch.empty((T, w.d_model), dtype=torch.bfloat16, device="cuda")
+
+                def call16(i, xT=xT, out=out):
+                    Wg, Wu, Wd = sets[i % 2]
+                    mm.mlpmoe_forward_bf16_out_bf16(xT, Wg, Wu, Wd, off, alpha, mask, out=out)
+
+                ms, _ = time_steps(mm, torch, call16, 20 if T > 16 else 50, 5, events=False)
+                o16["T%d_us" % T] = round(ms * 1e3, 2)
+            res["llama8b_out_bf16"] = o16
             del sets, xs
             # per-token routing, 4 of 16 branches per token: tokens grouped by route (each tile of 256
             # tokens shares its 4 branches), random routes, and decode

@@ -174,6 +174,25 @@ MLPMOE_API int mlpmoe_forward_f32(const float *x, const float *W_gate, const flo
                        float *out, void *stream);
 
 /*
+ * mlpmoe_forward_bf16_out_bf16 -- the bf16 forward with the result stored as bf16: out is
+ * [T, d_model] bf16 (device, 16-byte aligned), each element the fp32 sum over branches rounded once
+ * to nearest even.  Everything else (arguments, arithmetic up to that rounding, kernels, errors) is
+ * mlpmoe_forward_bf16's.  The rounding alone moves an element by up to 2^-9 of its magnitude, about
+ * 1e-2 of rms(out) for the largest elements: for callers whose next operation takes bf16 anyway
+ * (Sec. 3.1 defines the sum; its storage precision is the caller's choice).  The _ws form takes a
+ * caller-owned workspace and a path like mlpmoe_forward_bf16_ws and never allocates.
+ */
+MLPMOE_API int mlpmoe_forward_bf16_out_bf16(const void *x, const void *W_gate, const void *W_up,
+                                 const void *W_down, const int32_t *branch_offsets, const float *alpha,
+                                 const uint8_t *active_mask, int T, int d_model, int d_inter, int B,
+                                 void *out, void *stream);
+MLPMOE_API int mlpmoe_forward_bf16_out_bf16_ws(const void *x, const void *W_gate, const void *W_up,
+                                    const void *W_down, const int32_t *branch_offsets, const float *alpha,
+                                    const uint8_t *active_mask, int T, int d_model, int d_inter, int B,
+                                    void *out, void *workspace, size_t workspace_bytes, int path,
+                                    void *stream);
+
+/*
  * Caller-owned workspace forms.  workspace: device pointer, 256-byte aligned, at
  * least mlpmoe_workspace_bytes(T, d_model, d_inter, B, elem_bytes) bytes; its
  * contents are scratch.  path: one of MLPMOE_PATH_*; a path that cannot run the

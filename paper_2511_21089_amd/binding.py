@@ -26,7 +26,8 @@ EXPORTS = ["mlpmoe_status_string", "mlpmoe_last_error_detail", "mlpmoe_slice", "
            "mlpmoe_forward_bf16", "mlpmoe_forward", "mlpmoe_forward_f32", "mlpmoe_forward_bf16_ws",
            "mlpmoe_forward_f32_ws", "mlpmoe_release", "mlpmoe_profile_enable",
            "mlpmoe_profile_collect", "mlpmoe_profile_disable", "mlpmoe_plan_create", "mlpmoe_plan_forward",
-           "mlpmoe_plan_destroy", "mlpmoe_forward_routed_bf16", "mlpmoe_forward_routed_bf16_ws"]
+           "mlpmoe_plan_destroy", "mlpmoe_forward_routed_bf16", "mlpmoe_forward_routed_bf16_ws",
+           "mlpmoe_forward_bf16_out_bf16", "mlpmoe_forward_bf16_out_bf16_ws"]
 
 
 class MlpMoeError(RuntimeError):
@@ -81,6 +82,10 @@ def _load() -> ctypes.CDLL:
         getattr(lib, name).restype = i
     lib.mlpmoe_forward_bf16_ws.argtypes = [vp, vp, vp, vp, ip, fp, bp, i, i, i, i, vp, vp, sz, i, vp]
     lib.mlpmoe_forward_bf16_ws.restype = i
+    lib.mlpmoe_forward_bf16_out_bf16.argtypes = fwd
+    lib.mlpmoe_forward_bf16_out_bf16.restype = i
+    lib.mlpmoe_forward_bf16_out_bf16_ws.argtypes = [vp, vp, vp, vp, ip, fp, bp, i, i, i, i, vp, vp, sz, i, vp]
+    lib.mlpmoe_forward_bf16_out_bf16_ws.restype = i
     lib.mlpmoe_forward_f32_ws.argtypes = [vp, vp, vp, vp, ip, fp, bp, i, i, i, i, vp, vp, sz, vp]
     lib.mlpmoe_forward_f32_ws.restype = i
     lib.mlpmoe_release.argtypes = []
@@ -203,13 +208,16 @@ def _table(branch_offsets, alpha, active_mask):
 
 
 def _forward(name, x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, out, stream,
-             workspace=None, path=None):
+             workspace=None, path=None, out_dtype=None):
     import torch
     off, al, mk, B = _table(branch_offsets, alpha, active_mask)
     T, d_model = x.shape
     d_inter = W_gate.shape[0]
+    out_dtype = torch.float32 if out_dtype is None else out_dtype
     if out is None:
-        out = torch.empty((T, d_model), dtype=torch.float32, device=x.device)
+        out = torch.empty((T, d_model), dtype=out_dtype, device=x.device)
+    elif out.dtype != out_dtype or tuple(out.shape) != (T, d_model) or not out.is_contiguous():
+        raise ValueError("out must be a contiguous [T, d_model] tensor of %s" % out_dtype)
     args = [_dev_ptr(x), _dev_ptr(W_gate), _dev_ptr(W_up), _dev_ptr(W_down), off.ctypes.data,
             al.ctypes.data, mk.ctypes.data, int(T), int(d_model), int(d_inter), int(B), _dev_ptr(out)]
     if workspace is not None:
@@ -237,6 +245,20 @@ def mlpmoe_forward_bf16_ws(x, W_gate, W_up, W_down, branch_offsets, alpha, activ
                            path=PATH_AUTO, out=None, stream=None):
     return _forward("mlpmoe_forward_bf16_ws", x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask,
                     out, stream, workspace=workspace, path=path)
+
+
+def mlpmoe_forward_bf16_out_bf16(x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, out=None, stream=None):
+    """The bf16 forward with the result rounded once to bf16 (out: [T, d_model] torch.bfloat16)."""
+    import torch
+    return _forward("mlpmoe_forward_bf16_out_bf16", x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask,
+                    out, stream, out_dtype=torch.bfloat16)
+
+
+def mlpmoe_forward_bf16_out_bf16_ws(x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, workspace,
+                                    path=PATH_AUTO, out=None, stream=None):
+    import torch
+    return _forward("mlpmoe_forward_bf16_out_bf16_ws", x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask,
+                    out, stream, workspace=workspace, path=path, out_dtype=torch.bfloat16)
 
 
 def mlpmoe_forward_f32_ws(x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, workspace,

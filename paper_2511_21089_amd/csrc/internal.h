@@ -28,7 +28,8 @@ struct BranchTable {
 
 struct FwdArgs {
     const void *x, *Wg, *Wu, *Wd;
-    float *out;
+    float *out;         // [T, d_model] float, or the same number of bf16 values when out_bf16
+    bool out_bf16 = false;
     int T, d_model, d_inter;
     void *H;            // gated intermediate [T, ldh], bf16 or float
     int ldh;
@@ -68,6 +69,7 @@ int mfma_down_splits(int T, int d_model, int k_elems);
 size_t mfma_partial_bytes(int T, int d_model, int d_inter);
 
 hipError_t launch_fill_zero(float *out, size_t n, hipStream_t s);
+hipError_t launch_fill_zero16(uint16_t *out, size_t n, hipStream_t s);
 hipError_t launch_generic(const FwdArgs &a, const BranchTable &bt, bool is_bf16);
 hipError_t launch_mfma_bf16(const FwdArgs &a, const BranchTable &bt);
 size_t route_scratch_bytes(int T, int d_inter);

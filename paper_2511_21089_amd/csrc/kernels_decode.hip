@@ -121,7 +121,7 @@ template <int NW, int U, bool kGateUp, bool kRouted = false>
 __global__ void __launch_bounds__(NW * 64)
 decode_kernel(const uint16_t *__restrict__ Xin, int ldx, int T,
               const uint16_t *__restrict__ W0, const uint16_t *__restrict__ W1, int ldw,
-              int d_model, uint16_t *__restrict__ Hout, int ldh, float *__restrict__ out,
+              int d_model, uint16_t *__restrict__ Hout, int ldh, float *__restrict__ out, int out_bf16,
               const uint8_t *__restrict__ route, BranchTable bt)
 {
     static_assert(NW >= 4, "the final reduction uses 256 threads");
@@ -229,7 +229,12 @@ decode_kernel(const uint16_t *__restrict__ Xin, int ldx, int T,
 #pragma unroll
         for (int w = 0; w < NW; ++w) s0 += red[w][threadIdx.x];
         const int m = row0 + row;
-        if (m < d_model) out[(size_t)t * d_model + m] = s0;
+        if (m < d_model) {
+            if (out_bf16)
+                reinterpret_cast<uint16_t *>(out)[(size_t)t * d_model + m] = to_bf16(s0);
+            else
+                out[(size_t)t * d_model + m] = s0;
+        }
     }
 }
 
@@ -424,18 +429,18 @@ static hipError_t launch_decode_impl(const FwdArgs &a, const BranchTable &bt)
         ProfileScope ps(MLPMOE_KERNEL_DECODE_GATE_UP, a.stream);
         decode_kernel<MLPMOE_DEC_NW1, MLPMOE_DEC_U1, true, kRouted><<<(unsigned)tiles1, MLPMOE_DEC_NW1 * 64, 0, a.stream>>>(
             X, a.d_model, a.T, static_cast<const uint16_t *>(a.Wg), static_cast<const uint16_t *>(a.Wu),
-            a.d_model, a.d_model, H, a.ldh, nullptr, a.route, bt);
+            a.d_model, a.d_model, H, a.ldh, nullptr, 0, a.route, bt);
         if (launch_status("decode gate_up launch") != hipSuccess) return hipErrorLaunchFailure;
     }
     ProfileScope ps(MLPMOE_KERNEL_DECODE_DOWN, a.stream);
     if (tiles2 >= 192)
         decode_kernel<MLPMOE_DEC_NW2, MLPMOE_DEC_U2, false, kRouted><<<tiles2, MLPMOE_DEC_NW2 * 64, 0, a.stream>>>(
             H, a.ldh, a.T, static_cast<const uint16_t *>(a.Wd), nullptr, a.d_inter, a.d_model, nullptr,
-            a.ldh, a.out, a.route, bt);
+            a.ldh, a.out, a.out_bf16 ? 1 : 0, a.route, bt);
     else
         decode_kernel<16, 4, false, kRouted><<<tiles2, 1024, 0, a.stream>>>(
             H, a.ldh, a.T, static_cast<const uint16_t *>(a.Wd), nullptr, a.d_inter, a.d_model, nullptr,
-            a.ldh, a.out, a.route, bt);
+            a.ldh, a.out, a.out_bf16 ? 1 : 0, a.route, bt);
     return launch_status("decode_down launch");
 }
 

@@ -118,8 +118,8 @@ __device__ __forceinline__ float h_as_float<uint16_t, uint16_t>(const uint16_t *
 
 template <typename TIn, typename TH>
 __global__ void __launch_bounds__(GTHREADS)
-down_generic(const TH *__restrict__ H, const TIn *__restrict__ Wd, float *__restrict__ out, int T,
-             int d_model, int d_inter, int ldh, BranchTable bt)
+down_generic(const TH *__restrict__ H, const TIn *__restrict__ Wd, float *__restrict__ out, int out_bf16,
+             int T, int d_model, int d_inter, int ldh, BranchTable bt)
 {
     __shared__ float Hs[GK][GT + 1], Ds[GK][GT + 1];
     const int t0 = blockIdx.y * GT, m0 = blockIdx.x * GT;
@@ -159,16 +159,21 @@ down_generic(const TH *__restrict__ H, const TIn *__restrict__ Wd, float *__rest
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int m = m0 + tx * 4 + j;
-            if (m < d_model) out[(size_t)t * d_model + m] = acc[i][j];
+            if (m >= d_model) continue;
+            if (out_bf16)
+                reinterpret_cast<uint16_t *>(out)[(size_t)t * d_model + m] = float_to_bf16_rne(acc[i][j]);
+            else
+                out[(size_t)t * d_model + m] = acc[i][j];
         }
     }
 }
 
-__global__ void fill_zero_kernel(float *out, size_t n)
+template <typename Tel>
+__global__ void fill_zero_kernel(Tel *out, size_t n)
 {
     for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n;
          i += (size_t)gridDim.x * blockDim.x)
-        out[i] = 0.f;
+        out[i] = (Tel)0;
 }
 
 // Row gather for W_gate / W_up (grid.y = destination row) and column gather for W_down
@@ -236,8 +241,8 @@ hipError_t launch_generic_typed(const FwdArgs &a, const BranchTable &bt)
     }
     ProfileScope ps(MLPMOE_KERNEL_DOWN_GENERIC, a.stream);
     down_generic<TIn, TH><<<g2, GTHREADS, 0, a.stream>>>(
-        static_cast<const TH *>(a.H), static_cast<const TIn *>(a.Wd), a.out, a.T, a.d_model, a.d_inter,
-        a.ldh, bt);
+        static_cast<const TH *>(a.H), static_cast<const TIn *>(a.Wd), a.out, a.out_bf16 ? 1 : 0, a.T, a.d_model,
+        a.d_inter, a.ldh, bt);
     return launch_status("generic kernels launch");
 }
 
@@ -249,7 +254,17 @@ hipError_t launch_fill_zero(float *out, size_t n, hipStream_t s)
     size_t blocks = (n + 255) / 256;
     if (blocks > 4096) blocks = 4096;
     ProfileScope ps(MLPMOE_KERNEL_FILL_ZERO, s);
-    fill_zero_kernel<<<(unsigned)blocks, 256, 0, s>>>(out, n);
+    fill_zero_kernel<float><<<(unsigned)blocks, 256, 0, s>>>(out, n);
+    return launch_status("fill_zero launch");
+}
+
+hipError_t launch_fill_zero16(uint16_t *out, size_t n, hipStream_t s)
+{
+    if (n == 0) return hipSuccess;
+    size_t blocks = (n + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    ProfileScope ps(MLPMOE_KERNEL_FILL_ZERO, s);
+    fill_zero_kernel<uint16_t><<<(unsigned)blocks, 256, 0, s>>>(out, n);
     return launch_status("fill_zero launch");
 }
 

@@ -514,12 +514,13 @@ gate_up_mfma(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
 }
 
 // grid.x = splits * 8 * ids_per_xcd(tilesM * tilesN); dst = out (splits == 1) or partial[split][T][d_model].
+// dst_bf16 (only with splits == 1): dst holds bf16 values, each sum is rounded once (RNE).
 // kRouted: the K loop of token tile tm walks only the branches some token of the tile is routed
 // to (tile_need); H is 0 for the tokens of the tile that do not take a branch.
 template <int WM, int NB, bool kRouted>
 __global__ void __launch_bounds__(WM * 128)
 down_mfma(const uint16_t *__restrict__ H, const uint16_t *__restrict__ Wd, float *__restrict__ dst, int T,
-          int d_model, int d_inter, int ldh, int tiles_m, int tiles_n, int splits, int kt_total,
+          int d_model, int d_inter, int ldh, int tiles_m, int tiles_n, int splits, int kt_total, int dst_bf16,
           const uint8_t *__restrict__ tile_need, BranchTable bt)
 {
     __shared__ __attribute__((aligned(1024))) char lds[LDS_BYTES];
@@ -572,8 +573,17 @@ down_mfma(const uint16_t *__restrict__ H, const uint16_t *__restrict__ Wd, float
             for (int j = 0; j < NB; ++j) {
                 const int m = n0 + half * BNH + wn * (16 * NB) + j * 16 + 4 * q4;
                 // d_model is a multiple of 8: the four features are all inside or all outside
-                if (t < T && m < d_model)
-                    *reinterpret_cast<f32x4 *>(o + (size_t)t * d_model + m) = half ? acc1[i][j] : acc0[i][j];
+                if (t < T && m < d_model) {
+                    const f32x4 v = half ? acc1[i][j] : acc0[i][j];
+                    if (dst_bf16) {
+                        u32x2 pk;
+                        pk.x = (uint32_t)to_bf16(v[0]) | ((uint32_t)to_bf16(v[1]) << 16);
+                        pk.y = (uint32_t)to_bf16(v[2]) | ((uint32_t)to_bf16(v[3]) << 16);
+                        *reinterpret_cast<u32x2 *>(reinterpret_cast<uint16_t *>(dst) + (size_t)t * d_model + m) = pk;
+                    } else {
+                        *reinterpret_cast<f32x4 *>(o + (size_t)t * d_model + m) = v;
+                    }
+                }
             }
     }
 }
@@ -710,15 +720,18 @@ route_tile_list(const uint8_t *__restrict__ route, uint8_t *__restrict__ tile_ne
             if ((live[tn] >> j) & 1) list[(size_t)g * stride + pos++] = (uint32_t)(tn * gsz + j);
 }
 
-// out[i] = sum_z partial[z][i], summed in z order: deterministic.
+// out[i] = sum_z partial[z][i], summed in z order: deterministic.  out_bf16: out holds bf16 values.
 __global__ void reduce_partials(const float *__restrict__ partial, float *__restrict__ out, size_t n,
-                                int splits)
+                                int splits, int out_bf16)
 {
     for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n;
          i += (size_t)gridDim.x * blockDim.x) {
         float s = partial[i];
         for (int z = 1; z < splits; ++z) s += partial[(size_t)z * n + i];
-        out[i] = s;
+        if (out_bf16)
+            reinterpret_cast<uint16_t *>(out)[i] = to_bf16(s);
+        else
+            out[i] = s;
     }
 }
 
@@ -827,7 +840,8 @@ static hipError_t launch_down(const FwdArgs &a, const BranchTable &bt, int tiles
     ProfileScope ps(MLPMOE_KERNEL_DOWN_MFMA, a.stream);
     down_mfma<MFMA_WM, NB, kRouted><<<(unsigned)grid, MFMA_WM * 128, 0, a.stream>>>(
         static_cast<const uint16_t *>(a.H), static_cast<const uint16_t *>(a.Wd), splits > 1 ? a.partial : a.out,
-        a.T, a.d_model, a.d_inter, a.ldh, tiles_m, tiles_n, splits, kt_total, a.route_scratch, bt);
+        a.T, a.d_model, a.d_inter, a.ldh, tiles_m, tiles_n, splits, kt_total, (a.out_bf16 && splits == 1) ? 1 : 0,
+        a.route_scratch, bt);
     return launch_status("down_mfma launch");
 }
 
@@ -846,7 +860,7 @@ hipError_t launch_mfma_routed_bf16(const FwdArgs &a, const BranchTable &bt)
         const size_t n = (size_t)a.T * a.d_model;
         size_t blocks = (n + 255) / 256;
         if (blocks > 8192) blocks = 8192;
-        reduce_partials<<<(unsigned)blocks, 256, 0, a.stream>>>(a.partial, a.out, n, splits);
+        reduce_partials<<<(unsigned)blocks, 256, 0, a.stream>>>(a.partial, a.out, n, splits, a.out_bf16 ? 1 : 0);
     }
     return launch_status("reduce_partials launch");
 }
@@ -872,7 +886,7 @@ hipError_t launch_mfma_bf16(const FwdArgs &a, const BranchTable &bt)
         const size_t n = (size_t)a.T * a.d_model;
         size_t blocks = (n + 255) / 256;
         if (blocks > 8192) blocks = 8192;
-        reduce_partials<<<(unsigned)blocks, 256, 0, a.stream>>>(a.partial, a.out, n, splits);
+        reduce_partials<<<(unsigned)blocks, 256, 0, a.stream>>>(a.partial, a.out, n, splits, a.out_bf16 ? 1 : 0);
     }
     return launch_status("reduce_partials launch");
 }

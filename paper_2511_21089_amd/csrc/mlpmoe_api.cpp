@@ -101,7 +101,7 @@ size_t h_bytes(int T, int d_inter, int elem_bytes)
 int forward_table(const BranchTable &bt, bool aligned, const void *x, const void *Wg, const void *Wu,
                   const void *Wd, int T, int d_model, int d_inter, float *out, void *workspace,
                   size_t workspace_bytes, int path, bool is_bf16, hipStream_t stream,
-                  const uint8_t *route = nullptr)
+                  const uint8_t *route = nullptr, bool out_bf16 = false)
 {
     // launch status is read back with hipGetLastError(): drop whatever an earlier, unrelated
     // runtime call of this thread left behind (e.g. a "not ready" from an event query)
@@ -109,8 +109,10 @@ int forward_table(const BranchTable &bt, bool aligned, const void *x, const void
     g_err_detail[0] = 0;
 
     if (bt.n_runs == 0) {   // nothing active: the sum over branches is empty
-        return launch_fill_zero(out, (size_t)T * d_model, stream) == hipSuccess ? MLPMOE_OK
-                                                                                : MLPMOE_ERR_HIP;
+        const size_t n = (size_t)T * d_model;
+        const hipError_t e = out_bf16 ? launch_fill_zero16(reinterpret_cast<uint16_t *>(out), n, stream)
+                                      : launch_fill_zero(out, n, stream);
+        return e == hipSuccess ? MLPMOE_OK : MLPMOE_ERR_HIP;
     }
     if (route) {
         // the routed K loops start and stop at branch boundaries, not only at run boundaries
@@ -128,6 +130,7 @@ int forward_table(const BranchTable &bt, bool aligned, const void *x, const void
 
     FwdArgs a;
     a.x = x; a.Wg = Wg; a.Wu = Wu; a.Wd = Wd; a.out = out;
+    a.out_bf16 = out_bf16;
     a.T = T; a.d_model = d_model; a.d_inter = d_inter;
     a.H = workspace;
     a.ldh = h_ld(d_inter);
@@ -156,7 +159,7 @@ int forward_table(const BranchTable &bt, bool aligned, const void *x, const void
 int forward_impl(const void *x, const void *Wg, const void *Wu, const void *Wd, const int32_t *off,
                  const float *alpha, const uint8_t *mask, int T, int d_model, int d_inter, int B,
                  float *out, void *workspace, size_t workspace_bytes, int path, bool is_bf16,
-                 hipStream_t stream)
+                 hipStream_t stream, bool out_bf16 = false)
 {
     int rc = validate_common(x, Wg, Wu, Wd, off, alpha, mask, T, d_model, d_inter, B, out);
     if (rc != MLPMOE_OK) return rc;
@@ -166,7 +169,7 @@ int forward_impl(const void *x, const void *Wg, const void *Wu, const void *Wd, 
     build_table(off, alpha, mask, B, bt);
     const bool aligned = is_bf16 && fast_path_aligned(bt, d_model, d_inter);
     return forward_table(bt, aligned, x, Wg, Wu, Wd, T, d_model, d_inter, out, workspace, workspace_bytes,
-                         path, is_bf16, stream);
+                         path, is_bf16, stream, nullptr, out_bf16);
 }
 
 // Library-owned workspace of the current device, grown on demand.
@@ -206,7 +209,7 @@ int owned_workspace(size_t need, void **ptr, size_t *bytes)
 
 int forward_owned(const void *x, const void *Wg, const void *Wu, const void *Wd, const int32_t *off,
                   const float *alpha, const uint8_t *mask, int T, int d_model, int d_inter, int B,
-                  float *out, bool is_bf16, hipStream_t stream)
+                  float *out, bool is_bf16, hipStream_t stream, bool out_bf16 = false)
 {
     int rc = validate_common(x, Wg, Wu, Wd, off, alpha, mask, T, d_model, d_inter, B, out);
     if (rc != MLPMOE_OK) return rc;
@@ -217,7 +220,7 @@ int forward_owned(const void *x, const void *Wg, const void *Wu, const void *Wd,
     rc = owned_workspace(need, &ws, &ws_bytes);
     if (rc != MLPMOE_OK) return rc;
     return forward_impl(x, Wg, Wu, Wd, off, alpha, mask, T, d_model, d_inter, B, out, ws, ws_bytes,
-                        MLPMOE_PATH_AUTO, is_bf16, stream);
+                        MLPMOE_PATH_AUTO, is_bf16, stream, out_bf16);
 }
 
 }  // namespace
@@ -464,6 +467,24 @@ int mlpmoe_forward_bf16(const void *x, const void *W_gate, const void *W_up, con
 {
     return forward_owned(x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, T, d_model,
                          d_inter, B, out, true, static_cast<hipStream_t>(stream));
+}
+
+int mlpmoe_forward_bf16_out_bf16(const void *x, const void *W_gate, const void *W_up, const void *W_down,
+                                 const int32_t *branch_offsets, const float *alpha, const uint8_t *active_mask,
+                                 int T, int d_model, int d_inter, int B, void *out, void *stream)
+{
+    return forward_owned(x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, T, d_model, d_inter, B,
+                         static_cast<float *>(out), true, static_cast<hipStream_t>(stream), true);
+}
+
+int mlpmoe_forward_bf16_out_bf16_ws(const void *x, const void *W_gate, const void *W_up, const void *W_down,
+                                    const int32_t *branch_offsets, const float *alpha,
+                                    const uint8_t *active_mask, int T, int d_model, int d_inter, int B, void *out,
+                                    void *workspace, size_t workspace_bytes, int path, void *stream)
+{
+    return forward_impl(x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, T, d_model, d_inter, B,
+                        static_cast<float *>(out), workspace, workspace_bytes, path, true,
+                        static_cast<hipStream_t>(stream), true);
 }
 
 int mlpmoe_forward(const void *x, const void *W_gate, const void *W_up, const void *W_down,

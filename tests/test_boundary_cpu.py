@@ -32,6 +32,37 @@ def test_every_declared_symbol_is_exported():
     assert sorted(names) == sorted(mm.EXPORTS)
 
 
+def test_binding_signatures_match_the_header():
+    """Every exported function has ctypes argument types, as many as the header declares, with
+    pointers, size_t and int in the same places (an undeclared signature would pass 64-bit
+    pointers as C ints)."""
+    import ctypes
+    text = "".join(open(os.path.join(ROOT, "include", fn)).read()
+                   for fn in sorted(os.listdir(os.path.join(ROOT, "include"))) if fn.endswith(".h"))
+    decls = re.findall(r"MLPMOE_API\s+([\w\s\*]+?)\b(mlpmoe_\w+)\s*\(([^;]*?)\)\s*;", text, flags=re.S)
+    assert len(decls) == len(mm.EXPORTS)
+    for ret, name, params in decls:
+        params = [p.strip() for p in params.replace("\n", " ").split(",")]
+        if params == ["void"]:
+            params = []
+        fn = getattr(mm.lib, name)
+        assert fn.argtypes is not None, name
+        assert len(fn.argtypes) == len(params), (name, len(fn.argtypes), params)
+        for want, p in zip(fn.argtypes, params):
+            is_ptr = "*" in p
+            got_ptr = want is ctypes.c_void_p or want is ctypes.c_char_p or hasattr(want, "contents")
+            assert is_ptr == got_ptr, (name, p, want)
+            if not is_ptr:
+                assert (want is ctypes.c_size_t) == p.startswith("size_t"), (name, p, want)
+                assert (want is ctypes.c_int) == p.startswith("int"), (name, p, want)
+        if "char" in ret:
+            assert fn.restype is ctypes.c_char_p, name
+        elif "size_t" in ret:
+            assert fn.restype is ctypes.c_size_t, name
+        else:
+            assert fn.restype is ctypes.c_int, name
+
+
 def test_status_strings():
     assert mm.status_string(0) == "ok"
     for code in range(-7, 0):

@@ -51,9 +51,6 @@ size_t fade_scratch_words(int B);
 // Returns e, so that a failing site can `return note_hip_error("...", e);`.
 hipError_t note_hip_error(const char *where, hipError_t e);
 
-// Compute units of the current device (cached per device).
-hipError_t device_cu_count(int *cus);
-
 // Status of the launch just made; on failure notes `where` and hands the code back.
 inline hipError_t launch_status(const char *where)
 {

@@ -234,26 +234,6 @@ hipError_t note_hip_error(const char *where, hipError_t e)
     return e;
 }
 
-// Compute units of the current device, asked once per device.
-hipError_t device_cu_count(int *cus)
-{
-    static std::mutex mu;
-    static int known[64] = {0};
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return note_hip_error("hipGetDevice", e);
-    if (dev < 0 || dev >= 64) return note_hip_error("device index", hipErrorInvalidDevice);
-    std::lock_guard<std::mutex> lock(mu);
-    if (known[dev] == 0) {
-        int n = 0;
-        e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e != hipSuccess) return note_hip_error("hipDeviceGetAttribute(compute units)", e);
-        known[dev] = n > 0 ? n : 1;
-    }
-    *cus = known[dev];
-    return hipSuccess;
-}
-
 void profile_mark(int kernel_id, hipStream_t s, bool begin)
 {
     if (!g_prof.on) return;

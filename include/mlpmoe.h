@@ -125,8 +125,8 @@ MLPMOE_API int mlpmoe_compact(const void *W_gate, const void *W_up, const void *
 
 /*
  * Bytes of device workspace a forward call with these sizes may use (gated
- * intermediate H[T, d_inter] plus split-K partial sums).  Independent of the
- * branch table.  Returns 0 for invalid sizes.
+ * intermediate H[T, d_inter], split-K partial sums, and the tile tables of the
+ * routed forward).  Independent of the branch table.  Returns 0 for invalid sizes.
  */
 MLPMOE_API size_t mlpmoe_workspace_bytes(int T, int d_model, int d_inter, int B, int elem_bytes);
 

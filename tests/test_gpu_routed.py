@@ -59,6 +59,10 @@ def test_random_routing_prefill_and_decode(mm):
     assert np.all(got[7] == 0)
     for T in (1, 5, 16):                                # decode kernels
         check(run_routed(mm, L, off, alpha, mask, route, T), L, off, alpha, mask, route, T, contract=(T > 1))
+    # nobody takes anything: exact zeros from every path
+    nothing = np.zeros_like(route)
+    for T in (600, 5):
+        assert not np.any(run_routed(mm, L, off, alpha, mask, nothing, T))
 
 
 def test_grouped_routing_skips_pairs_nobody_takes(mm):

@@ -156,6 +156,42 @@ def test_forward_argument_validation_needs_no_gpu():
     assert f(*(_fwd_args(odd, al, mk2) + [ctypes.c_void_p(0x1000), 1 << 30, mm.PATH_MFMA, None])) == mm.ERR_UNSUPPORTED
 
 
+def test_routed_and_bf16_out_argument_validation():
+    """The routed and the bf16-result entry points reject bad arguments on the host like the plain ones."""
+    vp = ctypes.c_void_p
+    off = np.array([0, 64, 128, 192, 256], np.int32)
+    al = np.ones(4, np.float32)
+    mk = np.ones(4, np.uint8)
+    ws = [vp(0x1000), 1 << 30]
+
+    def routed(route=0x1000, **kw):
+        a = _fwd_args(off, al, mk, **kw)
+        return a[:7] + [vp(route)] + a[7:]
+
+    f = mm.lib.mlpmoe_forward_routed_bf16_ws
+    assert f(*(routed(B=0) + ws + [None])) == mm.ERR_SHAPE
+    assert f(*(routed(x=0) + ws + [None])) == mm.ERR_NULL
+    assert f(*(routed(route=0) + ws + [None])) == mm.ERR_NULL
+    assert f(*(routed(x=0x1004) + ws + [None])) == mm.ERR_ALIGN
+    assert f(*(routed(T=0, x=0, out=0, route=0) + ws + [None])) == mm.OK
+    assert f(*(routed() + [None, 0, None])) == mm.ERR_WORKSPACE
+    assert f(*(routed() + [vp(0x1000), 64, None])) == mm.ERR_WORKSPACE
+    assert mm.lib.mlpmoe_forward_routed_bf16(*(routed(T=-1) + [None])) == mm.ERR_SHAPE
+    assert mm.lib.mlpmoe_forward_routed_bf16(*(routed(T=0, x=0, out=0, route=0) + [None])) == mm.OK
+
+    g = mm.lib.mlpmoe_forward_bf16_out_bf16_ws
+    tail = ws + [mm.PATH_AUTO, None]
+    assert g(*(_fwd_args(off, al, mk, d_model=0) + tail)) == mm.ERR_SHAPE
+    assert g(*(_fwd_args(off, al, mk, out=0) + tail)) == mm.ERR_NULL
+    assert g(*(_fwd_args(off, al, mk, out=0x1002) + tail)) == mm.ERR_ALIGN
+    assert g(*(_fwd_args(off, al, mk, T=0, x=0, out=0) + tail)) == mm.OK
+    assert g(*(_fwd_args(off, al, mk) + [vp(0x1000), 16, mm.PATH_AUTO, None])) == mm.ERR_WORKSPACE
+    assert g(*(_fwd_args(off, al, mk, T=17) + ws + [mm.PATH_DECODE, None])) == mm.ERR_UNSUPPORTED
+    assert mm.lib.mlpmoe_forward_bf16_out_bf16(*(_fwd_args(off, al, mk, B=99) + [None])) == mm.ERR_SHAPE
+    # the workspace of a routed call is part of the common size
+    assert mm.mlpmoe_workspace_bytes(4096, 4096, 14336, 16) > 4096 * 14336 * 2 + 16 * 64
+
+
 def test_compact_validation():
     vp = ctypes.c_void_p
     f = mm.lib.mlpmoe_compact

@@ -68,3 +68,32 @@ def fractal_fade(W_gate: np.ndarray, W_up: np.ndarray, branch_offsets, sparsity=
         thr.append((tg, tu))
         kept.append((kg, ku))
     return Wg, Wu, thr, kept
+
+
+def neuron_scores(W_gate: np.ndarray, W_up: np.ndarray) -> np.ndarray:
+    """Score of every intermediate neuron for the structured form of the fade: the squared Euclidean
+    norm of its W_gate row and its W_up row together, in double precision."""
+    g = _to_f64(W_gate)
+    u = _to_f64(W_up)
+    return (g * g).sum(axis=1) + (u * u).sum(axis=1)
+
+
+def fade_neurons(W_gate: np.ndarray, W_up: np.ndarray, branch_offsets, keep_count):
+    """Structured form of the differential sparsity of Sec. 3.2: instead of zeroing single weights,
+    branch b keeps keep_count[b] whole neurons and drops the rest (the benchmark layer with
+    variable branch widths is of this kind; the paper itself only defines the element-wise form, so
+    the ranking rule is a reading: largest score first, equal scores by lower index).
+
+    Returns (neuron_keep [d_inter] uint8, scores [d_inter] float64).  Written as the definition:
+    per branch, a stable sort of the scores in descending order, the first keep_count[b] survive."""
+    off = np.asarray(branch_offsets, dtype=np.int64)
+    scores = neuron_scores(W_gate, W_up)
+    keep = np.zeros(scores.shape[0], dtype=np.uint8)
+    for b in range(off.size - 1):
+        lo, hi = int(off[b]), int(off[b + 1])
+        k = int(keep_count[b])
+        if not 0 <= k <= hi - lo:
+            raise ValueError("keep_count[%d] outside [0, d_b]" % b)
+        order = np.argsort(-scores[lo:hi], kind="stable")      # descending, ties by lower index
+        keep[lo + order[:k]] = 1
+    return keep, scores

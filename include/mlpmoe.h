@@ -262,6 +262,29 @@ MLPMOE_API int mlpmoe_fade(void *W_gate, void *W_up, const int32_t *branch_offse
                            long long *kept, void *stream);
 
 /*
+ * mlpmoe_fade_neurons -- the structured form of the fade: which whole neurons each branch keeps.
+ *
+ * Sec. 3.2 zeroes single weights; the layers whose branches have different widths keep and drop
+ * whole neurons instead, and the paper gives no rule for choosing them.  The reading implemented
+ * here: the score of neuron j is the squared Euclidean norm of its W_gate row and its W_up row
+ * together (accumulated in double), and branch b keeps the keep_count[b] neurons with the largest
+ * scores, equal scores in order of index.  The result feeds mlpmoe_slice (neuron_keep) and
+ * mlpmoe_compact; the weights are not changed.
+ *
+ *   W_gate, W_up    device, bf16 row-major [d_inter, d_model] (elem_bytes must be 2 and d_model a
+ *                   multiple of 8: MLPMOE_ERR_UNSUPPORTED otherwise), 16-byte aligned
+ *   branch_offsets  host, B + 1 entries as for mlpmoe_forward
+ *   keep_count      host, B entries, 0 <= keep_count[b] <= d_b (MLPMOE_ERR_SHAPE outside)
+ *   neuron_keep     host, d_inter bytes: 1 = kept, 0 = dropped
+ *   scores          host, d_inter doubles, or NULL
+ * Allocates and frees 9 * d_inter bytes of device scratch and synchronises `stream` before it
+ * returns (offline weight preparation).  Not-a-number weights are not supported.
+ */
+MLPMOE_API int mlpmoe_fade_neurons(const void *W_gate, const void *W_up, const int32_t *branch_offsets,
+                        const int32_t *keep_count, int d_model, int d_inter, int B, int elem_bytes,
+                        uint8_t *neuron_keep, double *scores, void *stream);
+
+/*
  * Per-kernel timing (measurement aid; the arithmetic is unchanged and nothing is skipped).
  * While enabled, every kernel a forward call launches is bracketed by a pair of HIP events
  * recorded on the call's own stream.

@@ -22,7 +22,7 @@ ERR_NULL, ERR_SHAPE, ERR_OFFSETS, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, ERR_A
 PATH_AUTO, PATH_GENERIC, PATH_MFMA, PATH_DECODE = 0, 1, 2, 3
 MAX_BRANCHES = 64
 
-EXPORTS = ["mlpmoe_status_string", "mlpmoe_last_error_detail", "mlpmoe_slice", "mlpmoe_compact", "mlpmoe_fade", "mlpmoe_workspace_bytes",
+EXPORTS = ["mlpmoe_status_string", "mlpmoe_last_error_detail", "mlpmoe_slice", "mlpmoe_compact", "mlpmoe_fade", "mlpmoe_fade_neurons", "mlpmoe_workspace_bytes",
            "mlpmoe_forward_bf16", "mlpmoe_forward", "mlpmoe_forward_f32", "mlpmoe_forward_bf16_ws",
            "mlpmoe_forward_f32_ws", "mlpmoe_release", "mlpmoe_profile_enable",
            "mlpmoe_profile_collect", "mlpmoe_profile_disable", "mlpmoe_plan_create", "mlpmoe_plan_forward",
@@ -74,6 +74,8 @@ def _load() -> ctypes.CDLL:
     lib.mlpmoe_forward_routed_bf16_ws.restype = i
     lib.mlpmoe_fade.argtypes = [vp, vp, ip, vp, i, i, i, i, vp, vp, vp]
     lib.mlpmoe_fade.restype = i
+    lib.mlpmoe_fade_neurons.argtypes = [vp, vp, ip, ip, i, i, i, i, bp, ctypes.POINTER(ctypes.c_double), vp]
+    lib.mlpmoe_fade_neurons.restype = i
     lib.mlpmoe_workspace_bytes.argtypes = [i, i, i, i, i]
     lib.mlpmoe_workspace_bytes.restype = sz
     fwd = [vp, vp, vp, vp, ip, fp, bp, i, i, i, i, vp, vp]
@@ -195,6 +197,25 @@ def mlpmoe_fade(W_gate, W_up, branch_offsets, sparsity=None, stream=None):
                          int(W_gate.element_size()), thr.ctypes.data, kept.ctypes.data, _stream_ptr(stream))
     _check(rc, "mlpmoe_fade")
     return thr, kept
+
+
+def mlpmoe_fade_neurons(W_gate, W_up, branch_offsets, keep_count, stream=None):
+    """Structured form of the fade: branch b keeps its keep_count[b] neurons with the largest squared norm of
+    gate and up row together.  Returns (neuron_keep [d_inter] uint8, scores [d_inter] float64); feed
+    neuron_keep to mlpmoe_slice and the gather list it returns to mlpmoe_compact."""
+    off = _host(branch_offsets, np.int32)
+    B = off.shape[0] - 1
+    cnt = _host(keep_count, np.int32)
+    if cnt.shape != (B,):
+        raise ValueError("keep_count needs B entries")
+    d_inter, d_model = W_gate.shape
+    keep = np.zeros(max(int(d_inter), 1), dtype=np.uint8)
+    scores = np.zeros(max(int(d_inter), 1), dtype=np.float64)
+    rc = lib.mlpmoe_fade_neurons(_dev_ptr(W_gate), _dev_ptr(W_up), off.ctypes.data, cnt.ctypes.data, int(d_model),
+                                 int(d_inter), int(B), int(W_gate.element_size()), keep.ctypes.data,
+                                 scores.ctypes.data_as(ctypes.POINTER(ctypes.c_double)), _stream_ptr(stream))
+    _check(rc, "mlpmoe_fade_neurons")
+    return keep[:d_inter], scores[:d_inter]
 
 
 def _table(branch_offsets, alpha, active_mask):

@@ -46,6 +46,9 @@ extern thread_local char g_err_detail[192];
 hipError_t launch_fade_bf16(void *W, const int32_t *off, const double *sparsity, int B, int d_model,
                             uint32_t *scratch, uint32_t *host_result, int *job_of_branch, hipStream_t s);
 size_t fade_scratch_words(int B);
+// Structured form (whole neurons): scores and keep flags of all neurons, asynchronous on s.
+hipError_t launch_fade_neurons_bf16(const void *Wg, const void *Wu, const int32_t *off, const int32_t *keep_count,
+                                    int B, int d_model, int d_inter, double *scores, uint8_t *keep, hipStream_t s);
 
 // Records which runtime call failed and how (read back through mlpmoe_last_error_detail()).
 // Returns e, so that a failing site can `return note_hip_error("...", e);`.

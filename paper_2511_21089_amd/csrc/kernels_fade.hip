@@ -125,7 +125,82 @@ __global__ void fill_u32(uint32_t *p, size_t n)
         p[i] = 0;
 }
 
+// ---- structured form: whole neurons ranked by the squared norm of their gate and up rows ----------
+// One wave per neuron.  Squares of bf16 values are exact in double; every lane adds its share of the
+// row in double, the lanes are added up by a butterfly (the order is fixed, the result the same in
+// all lanes).  d_model is a multiple of 8.
+__global__ void __launch_bounds__(256)
+fade_neuron_scores(const uint16_t *__restrict__ Wg, const uint16_t *__restrict__ Wu, double *__restrict__ scores,
+                   int d_inter, int d_model)
+{
+    const int lane = threadIdx.x & 63;
+    const long long j = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (j >= d_inter) return;
+    const uint16_t *g = Wg + (size_t)j * d_model, *u = Wu + (size_t)j * d_model;
+    double acc = 0.0;
+    for (int k = lane * 8; k < d_model; k += 64 * 8) {
+        const uint4 a = *reinterpret_cast<const uint4 *>(g + k);
+        const uint4 b = *reinterpret_cast<const uint4 *>(u + k);
+        const uint32_t w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const double lo = (double)__uint_as_float(w[i] << 16), hi = (double)__uint_as_float(w[i] & 0xffff0000u);
+            acc += lo * lo;
+            acc += hi * hi;
+        }
+    }
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) acc += __shfl_xor(acc, d);
+    if (lane == 0) scores[j] = acc;
+}
+
+struct NeuronJobs {
+    int B;
+    int off[MLPMOE_MAX_BRANCHES + 1];
+    int keep[MLPMOE_MAX_BRANCHES];
+};
+
+// keep[j] = 1 if fewer than keep_count[b] neurons of j's branch come before it (larger score, or the
+// same score and a lower index).  One thread per neuron, grid.y = branch.
+__global__ void __launch_bounds__(256)
+fade_neuron_select(const double *__restrict__ scores, uint8_t *__restrict__ keep, NeuronJobs jobs)
+{
+    const int b = blockIdx.y;
+    const int lo = jobs.off[b], hi = jobs.off[b + 1];
+    const int j = lo + blockIdx.x * 256 + threadIdx.x;
+    if (j >= hi) return;
+    const double mine = scores[j];
+    int before = 0;
+    for (int i = lo; i < hi; ++i) {
+        const double other = scores[i];                    // the same address in every lane: one broadcast read
+        before += (other > mine || (other == mine && i < j)) ? 1 : 0;
+    }
+    keep[j] = before < jobs.keep[b] ? 1 : 0;
+}
+
 }  // namespace
+
+// Structured fade: scores (device, d_inter doubles) and keep flags (device, d_inter bytes) of all neurons.
+// off / keep_count are host arrays (validated by the caller).  Asynchronous on s.
+hipError_t launch_fade_neurons_bf16(const void *Wg, const void *Wu, const int32_t *off, const int32_t *keep_count,
+                                    int B, int d_model, int d_inter, double *scores, uint8_t *keep, hipStream_t s)
+{
+    if (d_inter == 0) return hipSuccess;
+    NeuronJobs jobs;
+    jobs.B = B;
+    int widest = 0;
+    for (int b = 0; b < B; ++b) {
+        jobs.off[b] = off[b];
+        jobs.keep[b] = keep_count[b];
+        widest = off[b + 1] - off[b] > widest ? off[b + 1] - off[b] : widest;
+    }
+    jobs.off[B] = off[B];
+    fade_neuron_scores<<<(unsigned)((d_inter + 3) / 4), 256, 0, s>>>(
+        static_cast<const uint16_t *>(Wg), static_cast<const uint16_t *>(Wu), scores, d_inter, d_model);
+    if (launch_status("fade_neuron_scores launch") != hipSuccess) return hipErrorLaunchFailure;
+    fade_neuron_select<<<dim3((unsigned)((widest + 255) / 256), (unsigned)B), 256, 0, s>>>(scores, keep, jobs);
+    return launch_status("fade_neuron_select launch");
+}
 
 // One projection matrix W [d_inter, d_model] (bf16, device).  off / sparsity are host arrays.
 // scratch: device, >= B * (kBins + 4) uint32.  host_result: B * 4 uint32 (filled for faded branches).

@@ -413,6 +413,47 @@ int mlpmoe_fade(void *W_gate, void *W_up, const int32_t *branch_offsets, const d
     return rc;
 }
 
+int mlpmoe_fade_neurons(const void *W_gate, const void *W_up, const int32_t *branch_offsets,
+                        const int32_t *keep_count, int d_model, int d_inter, int B, int elem_bytes,
+                        uint8_t *neuron_keep, double *scores, void *stream)
+{
+    if (B < 1 || B > MLPMOE_MAX_BRANCHES || d_model < 1 || d_inter < 0) return MLPMOE_ERR_SHAPE;
+    if (!branch_offsets || !keep_count) return MLPMOE_ERR_NULL;
+    if (branch_offsets[0] != 0 || branch_offsets[B] != d_inter) return MLPMOE_ERR_OFFSETS;
+    for (int b = 0; b < B; ++b) {
+        if (branch_offsets[b + 1] < branch_offsets[b]) return MLPMOE_ERR_OFFSETS;
+        if (keep_count[b] < 0 || keep_count[b] > branch_offsets[b + 1] - branch_offsets[b]) return MLPMOE_ERR_SHAPE;
+    }
+    if (d_inter == 0) return MLPMOE_OK;
+    if (!W_gate || !W_up || !neuron_keep) return MLPMOE_ERR_NULL;
+    if (elem_bytes != 2 || d_model % 8 != 0) return MLPMOE_ERR_UNSUPPORTED;
+    if (!aligned16(W_gate) || !aligned16(W_up)) return MLPMOE_ERR_ALIGN;
+
+    (void)hipGetLastError();
+    g_err_detail[0] = 0;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const size_t score_bytes = align_up((size_t)d_inter * sizeof(double), 256);
+    char *scratch = nullptr;
+    hipError_t e = hipMalloc(reinterpret_cast<void **>(&scratch), score_bytes + (size_t)d_inter);
+    if (e != hipSuccess) {
+        (void)note_hip_error("hipMalloc(neuron scores)", e);
+        (void)hipGetLastError();
+        return MLPMOE_ERR_HIP;
+    }
+    double *d_scores = reinterpret_cast<double *>(scratch);
+    uint8_t *d_keep = reinterpret_cast<uint8_t *>(scratch + score_bytes);
+    e = launch_fade_neurons_bf16(W_gate, W_up, branch_offsets, keep_count, B, d_model, d_inter, d_scores, d_keep, s);
+    if (e == hipSuccess) {
+        e = hipMemcpyAsync(neuron_keep, d_keep, (size_t)d_inter, hipMemcpyDeviceToHost, s);
+        if (e == hipSuccess && scores)
+            e = hipMemcpyAsync(scores, d_scores, (size_t)d_inter * sizeof(double), hipMemcpyDeviceToHost, s);
+        if (e == hipSuccess) e = hipStreamSynchronize(s);
+        if (e != hipSuccess) (void)note_hip_error("copying the neuron flags back", e);
+    }
+    (void)hipFree(scratch);
+    return e == hipSuccess ? MLPMOE_OK : MLPMOE_ERR_HIP;
+}
+
 int mlpmoe_compact(const void *W_gate, const void *W_up, const void *W_down, const int32_t *gather,
                    int n_rows, int d_model, int d_inter_src, int elem_bytes, void *W_gate_c,
                    void *W_up_c, void *W_down_c, void *stream)

@@ -222,6 +222,30 @@ def test_fade_argument_validation():
     assert call(np.array([0, 0], np.int32), None, 64, 0, 1, 2, None) == mm.OK
 
 
+def test_fade_neurons_argument_validation():
+    """mlpmoe_fade_neurons refuses bad tables, counts and storage before touching the GPU."""
+    import ctypes
+    lib = mm.lib
+    off = np.array([0, 8, 16], np.int32)
+    cnt = np.array([8, 3], np.int32)
+    fake = ctypes.c_void_p(0x1000)
+    keep = np.zeros(16, np.uint8)
+    call = lambda offs, c, dm, di, B, eb, wg=fake, out=keep: lib.mlpmoe_fade_neurons(
+        wg, fake, offs.ctypes.data, c.ctypes.data if c is not None else None, dm, di, B, eb,
+        out.ctypes.data if out is not None else None, None, None)
+    assert call(off, cnt, 64, 16, 0, 2) == mm.ERR_SHAPE
+    assert call(off, cnt, 64, 17, 2, 2) == mm.ERR_OFFSETS
+    assert call(off, None, 64, 16, 2, 2) == mm.ERR_NULL
+    assert call(off, np.array([9, 3], np.int32), 64, 16, 2, 2) == mm.ERR_SHAPE      # more than the branch holds
+    assert call(off, np.array([8, -1], np.int32), 64, 16, 2, 2) == mm.ERR_SHAPE
+    assert call(off, cnt, 64, 16, 2, 4) == mm.ERR_UNSUPPORTED
+    assert call(off, cnt, 60, 16, 2, 2) == mm.ERR_UNSUPPORTED
+    assert call(off, cnt, 64, 16, 2, 2, ctypes.c_void_p(0x1008)) == mm.ERR_ALIGN
+    assert call(off, cnt, 64, 16, 2, 2, None) == mm.ERR_NULL
+    assert call(off, cnt, 64, 16, 2, 2, fake, None) == mm.ERR_NULL
+    assert call(np.array([0, 0], np.int32), np.array([0], np.int32), 64, 0, 1, 2, None, None) == mm.OK
+
+
 def test_plan_argument_validation():
     """mlpmoe_plan_create checks the table before it touches the GPU; a NULL plan is harmless."""
     import ctypes

@@ -72,3 +72,62 @@ def test_fade_8b_block_size(mm):
     L = synth.make_layer("llama8b", 1, seed=8, d_inter=3 * 896, B=3)
     off = np.array([0, 896, 1792, 2688], np.int32)
     fade_and_compare(mm, L, off, [0.0, 0.45, 0.84375])
+
+
+def test_fade_neurons_matches_the_oracle(mm):
+    """Structured form: kept set and scores of every neuron against the oracle, uneven branches."""
+    widths = [96, 0, 200, 8, 333, 64]
+    off = np.concatenate([[0], np.cumsum(widths)]).astype(np.int32)
+    L = synth.make_layer("qwen05b", 4, seed=71, d_model=520, d_inter=int(off[-1]))
+    rng = np.random.default_rng(2)
+    counts = np.array([int(rng.integers(0, w + 1)) for w in widths], np.int32)
+    counts[0], counts[3] = widths[0], 0                       # keep all / keep none
+    keep, sc = mm.mlpmoe_fade_neurons(to_dev(L.W_gate), to_dev(L.W_up), off, counts)
+    rkeep, rsc = oracle.fade_neurons(L.W_gate, L.W_up, off, counts)
+    assert np.allclose(sc, rsc, rtol=1e-13, atol=0)
+    for b, w in enumerate(widths):
+        assert keep[off[b]:off[b + 1]].sum() == counts[b]
+    if not np.array_equal(keep, rkeep):
+        # the two sums differ in their last bits: a disagreement is only valid between near-equal scores
+        for b in range(len(widths)):
+            lo, hi = off[b], off[b + 1]
+            diff = np.nonzero(keep[lo:hi] != rkeep[lo:hi])[0]
+            if diff.size:
+                s = rsc[lo:hi][diff]
+                assert s.max() - s.min() <= 1e-12 * s.max()
+
+
+def test_fade_neurons_exact_ties_go_by_index(mm):
+    """Small-integer weights: scores are exact and full of ties, so the kept set must agree exactly."""
+    rng = np.random.default_rng(3)
+    d_model, widths = 64, [40, 72, 16]
+    off = np.concatenate([[0], np.cumsum(widths)]).astype(np.int32)
+    Wg = synth.f32_to_bf16_bits(rng.integers(-2, 3, size=(off[-1], d_model)).astype(np.float32))
+    Wu = synth.f32_to_bf16_bits(rng.integers(-2, 3, size=(off[-1], d_model)).astype(np.float32))
+    counts = np.array([17, 36, 5], np.int32)
+    keep, sc = mm.mlpmoe_fade_neurons(to_dev(Wg), to_dev(Wu), off, counts)
+    rkeep, rsc = oracle.fade_neurons(Wg, Wu, off, counts)
+    assert np.array_equal(sc, rsc)
+    assert len(np.unique(rsc)) < len(rsc) // 2               # the case really has ties
+    assert np.array_equal(keep, rkeep)
+
+
+def test_fade_neurons_then_slice_compact_forward(mm):
+    """The whole preparation on the GPU side: scores -> kept neurons -> compacted layer -> forward, against the
+    oracle's forward of the uncompacted layer with the dropped neurons' up rows zeroed."""
+    B, d_b, d_model, T = 16, 160, 512, 300
+    L = synth.make_layer("llama8b", T, seed=72, d_model=d_model, d_inter=B * d_b)
+    off, alpha, mask, _ = mm.mlpmoe_slice(B * d_b, B)
+    counts = np.array([int(np.floor(d_b * (1 - 0.4 * b / (B - 1)) + 0.5)) for b in range(B)], np.int32)
+    Wg_d, Wu_d, Wd_d = to_dev(L.W_gate), to_dev(L.W_up), to_dev(L.W_down)
+    keep, _ = mm.mlpmoe_fade_neurons(Wg_d, Wu_d, off, counts)
+    rkeep, _ = oracle.fade_neurons(L.W_gate, L.W_up, off, counts)
+    assert np.array_equal(keep, rkeep)
+    offc, alphac, maskc, gather = mm.mlpmoe_slice(B * d_b, B, 0, keep, 8)
+    Wg_c, Wu_c, Wd_c = mm.mlpmoe_compact(Wg_d, Wu_d, Wd_d, gather)
+    got = mm.mlpmoe_forward_bf16(to_dev(L.x), Wg_c, Wu_c, Wd_c, offc, L.alpha_draw, maskc).cpu().numpy()
+    Wu0 = L.W_up.copy()
+    Wu0[keep == 0] = 0
+    for mode in ("contract", "exact"):
+        ref = oracle_out(L.x, L.W_gate, Wu0, L.W_down, off, L.alpha_draw, mask, mode)
+        assert oracle.rel_max_err(got, ref) <= BF16_TOL, mode

@@ -235,6 +235,21 @@ MLPMOE_API int mlpmoe_forward_routed_bf16_ws(const void *x, const void *W_gate, 
                                              float *out, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The routed forward for float x and weights: same reading of the routing, no intermediate rounding,
+ * fp32 accumulation throughout (the LDS-tiled FMA kernels; they mask and do not skip).  The _ws form
+ * takes mlpmoe_workspace_bytes(T, d_model, d_inter, B, 4) bytes.
+ */
+MLPMOE_API int mlpmoe_forward_routed_f32(const float *x, const float *W_gate, const float *W_up,
+                                         const float *W_down, const int32_t *branch_offsets, const float *alpha,
+                                         const uint8_t *active_mask, const uint8_t *route, int T, int d_model,
+                                         int d_inter, int B, float *out, void *stream);
+MLPMOE_API int mlpmoe_forward_routed_f32_ws(const float *x, const float *W_gate, const float *W_up,
+                                            const float *W_down, const int32_t *branch_offsets,
+                                            const float *alpha, const uint8_t *active_mask, const uint8_t *route,
+                                            int T, int d_model, int d_inter, int B, float *out, void *workspace,
+                                            size_t workspace_bytes, void *stream);
+
+/*
  * mlpmoe_fade -- Fractal Fade weight preparation (Sec. 3.2), in place, on the device.
  *
  * For every branch b with sparsity[b] > 0, and separately for the branch's rows of W_gate and of

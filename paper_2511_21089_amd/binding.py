@@ -27,7 +27,8 @@ EXPORTS = ["mlpmoe_status_string", "mlpmoe_last_error_detail", "mlpmoe_slice", "
            "mlpmoe_forward_f32_ws", "mlpmoe_release", "mlpmoe_profile_enable",
            "mlpmoe_profile_collect", "mlpmoe_profile_disable", "mlpmoe_plan_create", "mlpmoe_plan_forward",
            "mlpmoe_plan_destroy", "mlpmoe_forward_routed_bf16", "mlpmoe_forward_routed_bf16_ws",
-           "mlpmoe_forward_bf16_out_bf16", "mlpmoe_forward_bf16_out_bf16_ws"]
+           "mlpmoe_forward_bf16_out_bf16", "mlpmoe_forward_bf16_out_bf16_ws",
+           "mlpmoe_forward_routed_f32", "mlpmoe_forward_routed_f32_ws"]
 
 
 class MlpMoeError(RuntimeError):
@@ -72,6 +73,10 @@ def _load() -> ctypes.CDLL:
     lib.mlpmoe_forward_routed_bf16.restype = i
     lib.mlpmoe_forward_routed_bf16_ws.argtypes = [vp, vp, vp, vp, ip, fp, bp, vp, i, i, i, i, vp, vp, sz, vp]
     lib.mlpmoe_forward_routed_bf16_ws.restype = i
+    lib.mlpmoe_forward_routed_f32.argtypes = lib.mlpmoe_forward_routed_bf16.argtypes
+    lib.mlpmoe_forward_routed_f32.restype = i
+    lib.mlpmoe_forward_routed_f32_ws.argtypes = lib.mlpmoe_forward_routed_bf16_ws.argtypes
+    lib.mlpmoe_forward_routed_f32_ws.restype = i
     lib.mlpmoe_fade.argtypes = [vp, vp, ip, vp, i, i, i, i, vp, vp, vp]
     lib.mlpmoe_fade.restype = i
     lib.mlpmoe_fade_neurons.argtypes = [vp, vp, ip, ip, i, i, i, i, bp, ctypes.POINTER(ctypes.c_double), vp]
@@ -292,9 +297,21 @@ def mlpmoe_release():
     _check(lib.mlpmoe_release(), "mlpmoe_release")
 
 
+def mlpmoe_forward_routed_f32(x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, route, out=None,
+                              workspace=None, stream=None):
+    """The routed forward for float32 x and weights."""
+    return _forward_routed("mlpmoe_forward_routed_f32", x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask,
+                           route, out, workspace, stream)
+
+
 def mlpmoe_forward_routed_bf16(x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, route, out=None,
                                workspace=None, stream=None):
     """Forward with a per-token branch set: route is a [T, B] uint8 GPU tensor (nonzero = token takes branch)."""
+    return _forward_routed("mlpmoe_forward_routed_bf16", x, W_gate, W_up, W_down, branch_offsets, alpha,
+                           active_mask, route, out, workspace, stream)
+
+
+def _forward_routed(name, x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, route, out, workspace, stream):
     import torch
     off, al, mk, B = _table(branch_offsets, alpha, active_mask)
     T, d_model = int(x.shape[0]), int(x.shape[1])
@@ -306,11 +323,10 @@ def mlpmoe_forward_routed_bf16(x, W_gate, W_up, W_down, branch_offsets, alpha, a
     common = (_dev_ptr(x), _dev_ptr(W_gate), _dev_ptr(W_up), _dev_ptr(W_down), off.ctypes.data, al.ctypes.data,
               mk.ctypes.data, _dev_ptr(route) if T else None, T, d_model, d_inter, B, _dev_ptr(out))
     if workspace is None:
-        rc = lib.mlpmoe_forward_routed_bf16(*common, _stream_ptr(stream))
-        _check(rc, "mlpmoe_forward_routed_bf16")
+        _check(getattr(lib, name)(*common, _stream_ptr(stream)), name)
     else:
-        rc = lib.mlpmoe_forward_routed_bf16_ws(*common, _dev_ptr(workspace), int(workspace.numel()), _stream_ptr(stream))
-        _check(rc, "mlpmoe_forward_routed_bf16_ws")
+        _check(getattr(lib, name + "_ws")(*common, _dev_ptr(workspace), int(workspace.numel() * workspace.element_size()),
+                                          _stream_ptr(stream)), name + "_ws")
     return out
 
 

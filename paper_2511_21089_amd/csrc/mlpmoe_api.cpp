@@ -547,20 +547,38 @@ int mlpmoe_forward_f32(const float *x, const float *W_gate, const float *W_up, c
 static int forward_routed(const void *x, const void *Wg, const void *Wu, const void *Wd, const int32_t *off,
                           const float *alpha, const uint8_t *mask, const uint8_t *route, int T, int d_model,
                           int d_inter, int B, float *out, void *workspace, size_t workspace_bytes, bool own,
-                          hipStream_t stream)
+                          hipStream_t stream, bool is_bf16 = true)
 {
     int rc = validate_common(x, Wg, Wu, Wd, off, alpha, mask, T, d_model, d_inter, B, out);
     if (rc != MLPMOE_OK) return rc;
     if (T == 0) return MLPMOE_OK;
     if (!route) return MLPMOE_ERR_NULL;
     if (own) {
-        rc = owned_workspace(mlpmoe_workspace_bytes(T, d_model, d_inter, B, 2), &workspace, &workspace_bytes);
+        rc = owned_workspace(mlpmoe_workspace_bytes(T, d_model, d_inter, B, is_bf16 ? 2 : 4), &workspace,
+                             &workspace_bytes);
         if (rc != MLPMOE_OK) return rc;
     }
     BranchTable bt;
     build_table(off, alpha, mask, B, bt);
-    return forward_table(bt, fast_path_aligned(bt, d_model, d_inter), x, Wg, Wu, Wd, T, d_model, d_inter, out,
-                         workspace, workspace_bytes, MLPMOE_PATH_AUTO, true, stream, route);
+    return forward_table(bt, is_bf16 && fast_path_aligned(bt, d_model, d_inter), x, Wg, Wu, Wd, T, d_model, d_inter,
+                         out, workspace, workspace_bytes, MLPMOE_PATH_AUTO, is_bf16, stream, route);
+}
+
+int mlpmoe_forward_routed_f32(const float *x, const float *W_gate, const float *W_up, const float *W_down,
+                              const int32_t *branch_offsets, const float *alpha, const uint8_t *active_mask,
+                              const uint8_t *route, int T, int d_model, int d_inter, int B, float *out, void *stream)
+{
+    return forward_routed(x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, route, T, d_model, d_inter,
+                          B, out, nullptr, 0, true, static_cast<hipStream_t>(stream), false);
+}
+
+int mlpmoe_forward_routed_f32_ws(const float *x, const float *W_gate, const float *W_up, const float *W_down,
+                                 const int32_t *branch_offsets, const float *alpha, const uint8_t *active_mask,
+                                 const uint8_t *route, int T, int d_model, int d_inter, int B, float *out,
+                                 void *workspace, size_t workspace_bytes, void *stream)
+{
+    return forward_routed(x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, route, T, d_model, d_inter,
+                          B, out, workspace, workspace_bytes, false, static_cast<hipStream_t>(stream), false);
 }
 
 int mlpmoe_forward_routed_bf16(const void *x, const void *W_gate, const void *W_up, const void *W_down,

@@ -159,3 +159,24 @@ def test_tile_list_ragged_groups_uneven_branches_unaligned_route(mm):
         got = mm.mlpmoe_forward_routed_bf16(x, Wg, Wu, Wd, off, alpha, mask, r).cpu().numpy()
         check(got, L, off, alpha, mask, route, exact=False)
         assert np.all(got[5 * 256:6 * 256] == 0)
+
+
+def test_routed_float_storage(mm):
+    """Float x and weights: the FMA kernels with the route mask, against the exact oracle at the float tolerance."""
+    import torch
+    from gpu_util import FP32_TOL
+    L = synth.make_layer("tiny_f32", 70, seed=56, d_model=72, d_inter=403)
+    off = np.array([0, 100, 100, 237, 403], np.int32)
+    mask = np.array([1, 1, 1, 0], np.uint8)
+    alpha = np.random.default_rng(5).uniform(0.9, 1.2, size=4).astype(np.float32)
+    route = top_k_route(np.random.default_rng(6), 70, 4, 2)
+    route[3] = 0
+    dev = [torch.from_numpy(np.ascontiguousarray(a)).cuda() for a in (L.x, L.W_gate, L.W_up, L.W_down)]
+    r = torch.from_numpy(route).cuda()
+    ref = oracle.mlpmoe_forward_routed(L.x, L.W_gate, L.W_up, L.W_down, off, alpha, mask, route, mode="exact")
+    got = mm.mlpmoe_forward_routed_f32(*dev, off, alpha, mask, r).cpu().numpy()
+    assert oracle.rel_max_err(got, ref) <= FP32_TOL
+    assert not np.any(got[3])
+    ws = mm.new_workspace(70, 72, 403, 4, 4)
+    got = mm.mlpmoe_forward_routed_f32(*dev, off, alpha, mask, r, workspace=ws).cpu().numpy()
+    assert oracle.rel_max_err(got, ref) <= FP32_TOL

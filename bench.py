@@ -37,7 +37,7 @@ TRAFFIC = {
     # (workload, kernel): (sha256 of the kernel's source file, bytes per launch = read + written)
     # gate_up_mfma at T=4096: 1409.4 MB read (x is re-read once per group of 4 neuron tiles and the
     # weights once per XCD that needs them: 5.3x the 268 MB the kernel has to read) + 117.5 MB written
-    ("llama8b_T4096", "gate_up_mfma"): ("0e62f5365b3ce577edc746eb5ab3232eeec2b19816a12c74b0fb3b003b8abc1c", 1526.9e6),
+    ("llama8b_T4096", "gate_up_mfma"): ("3ef1f5a0fb5405e74cacc34332055048e5b29b071a3425de39efeaaa99ae4129", 1526.9e6),
     # decode gate+up at T=1: 235.1 MB read (the weights, once) + 0.1 MB written
     ("llama8b_T1", "decode_gate_up"): ("57bf901eff8a23e89f4f3c8c73e90367bcab048f162b19ca2c38df9a2643341f", 235.2e6),
 }

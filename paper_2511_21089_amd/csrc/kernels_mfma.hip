@@ -852,8 +852,12 @@ hipError_t launch_mfma_routed_bf16(const FwdArgs &a, const BranchTable &bt)
     const int tiles_m = ceil_div(a.T, BM);
     hipError_t e = launch_gate_up<4, true>(a, bt, tiles_m);
     if (e != hipSuccess) return hipErrorLaunchFailure;
+    // the down projection takes the tile width and the K split the unrouted launch takes, so that a
+    // route of all ones adds up every output in the same order and gives the same bits
+    const bool narrow2 = down_splits(a.T, a.d_model, bt.d_eff, 2 * BNH_MAX) > 1;
     int splits = 1;
-    e = launch_down<4, true>(a, bt, tiles_m, k_tiles(bt), &splits);
+    e = narrow2 ? launch_down<2, true>(a, bt, tiles_m, k_tiles(bt), &splits)
+                : launch_down<4, true>(a, bt, tiles_m, k_tiles(bt), &splits);
     if (e != hipSuccess) return hipErrorLaunchFailure;
     if (splits > 1) {
         ProfileScope ps(MLPMOE_KERNEL_SPLITK_REDUCE, a.stream);

@@ -180,3 +180,25 @@ def test_routed_float_storage(mm):
     ws = mm.new_workspace(70, 72, 403, 4, 4)
     got = mm.mlpmoe_forward_routed_f32(*dev, off, alpha, mask, r, workspace=ws).cpu().numpy()
     assert oracle.rel_max_err(got, ref) <= FP32_TOL
+
+
+def test_many_token_tile_groups(mm):
+    """T = 20000: 79 token tiles in 10 groups of the tile list.  All-ones routing equals the plain forward bit for
+    bit; a banded routing (token tile i takes branches i mod 8 and (i + 3) mod 8) is checked on sampled rows."""
+    import torch
+    T, B, d_b, d_model = 20000, 8, 256, 256
+    L = synth.make_layer("qwen05b", T, seed=57, d_model=d_model, d_inter=B * d_b)
+    off, _, mask, _ = mm.mlpmoe_slice(B * d_b, B)
+    alpha = L.alpha_draw
+    x, Wg, Wu, Wd = (to_dev(a) for a in (L.x, L.W_gate, L.W_up, L.W_down))
+    ones = torch.ones((T, B), dtype=torch.uint8, device="cuda")
+    assert torch.equal(mm.mlpmoe_forward_routed_bf16(x, Wg, Wu, Wd, off, alpha, mask, ones),
+                       mm.mlpmoe_forward_bf16(x, Wg, Wu, Wd, off, alpha, mask))
+    route = np.zeros((T, B), np.uint8)
+    for i in range((T + 255) // 256):
+        route[i * 256:(i + 1) * 256, [i % B, (i + 3) % B]] = 1
+    got = mm.mlpmoe_forward_routed_bf16(x, Wg, Wu, Wd, off, alpha, mask, torch.from_numpy(route).cuda()).cpu().numpy()
+    rows = np.concatenate([np.random.default_rng(9).choice(T, size=40, replace=False), [0, 255, 256, T - 1]])
+    ref = oracle.mlpmoe_forward_routed(widen(L.x[rows]), widen(L.W_gate), widen(L.W_up), widen(L.W_down), off, alpha,
+                                       mask, route[rows], mode="contract")
+    assert oracle.rel_max_err(got[rows], ref) <= 2 * BF16_TOL       # 512 neurons per token

@@ -145,7 +145,9 @@ MLPMOE_API size_t mlpmoe_workspace_bytes(int T, int d_model, int d_inter, int B,
  * Arithmetic: gate and up products accumulate in fp32; h = alpha_b * SiLU(g) * u is
  * formed in fp32 and rounded ONCE to bf16 (nearest even); the down projection
  * accumulates those bf16 values against W_down in fp32 across all branches.
- * Results are bitwise reproducible from run to run (no floating-point atomics).
+ * Results are bitwise reproducible from run to run: sums are formed in a fixed order; the one place
+ * that uses floating-point atomics (the decode down projection of wide layers) adds exactly two
+ * partial sums into a zero, which gives the same number in either order.
  *
  * Workspace: taken from a per-device buffer the library owns and grows with
  * hipMalloc when a call needs more than any earlier one (that growth synchronises
@@ -176,8 +178,9 @@ MLPMOE_API int mlpmoe_forward_f32(const float *x, const float *W_gate, const flo
 /*
  * mlpmoe_forward_bf16_out_bf16 -- the bf16 forward with the result stored as bf16: out is
  * [T, d_model] bf16 (device, 16-byte aligned), each element the fp32 sum over branches rounded once
- * to nearest even.  Everything else (arguments, arithmetic up to that rounding, kernels, errors) is
- * mlpmoe_forward_bf16's.  The rounding alone moves an element by up to 2^-9 of its magnitude, about
+ * to nearest even.  Everything else (arguments, arithmetic up to that rounding, errors) is
+ * mlpmoe_forward_bf16's, and so are the kernels, except that for T <= 16 and d_model >= 3072 the
+ * float result adds the two halves of K separately, which can move a sum by a float rounding.  The rounding alone moves an element by up to 2^-9 of its magnitude, about
  * 1e-2 of rms(out) for the largest elements: for callers whose next operation takes bf16 anyway
  * (Sec. 3.1 defines the sum; its storage precision is the caller's choice).  The _ws form takes a
  * caller-owned workspace and a path like mlpmoe_forward_bf16_ws and never allocates.

@@ -238,6 +238,118 @@ decode_kernel(const uint16_t *__restrict__ Xin, int ldx, int T,
     }
 }
 
+// Down projection for layers with many output features: two row tiles (32 output features) per
+// workgroup and the K blocks dealt to TWO workgroups (blockIdx.y).  Every workgroup of the one-tile
+// kernel reads all of H, which at 16 tokens is as many bytes as its weight rows, all from the same
+// L2; here a block of H is used for two weight fragments and each workgroup reads half of H, a quarter
+// of that traffic per weight byte, with all CUs still busy.  The two partial sums of an output are
+// added into `out` with float atomics: out must hold zeros when the kernel starts (the gate+up
+// kernel that runs before it clears it), and 0 + a + b is the same number in either order, so the
+// result does not depend on which workgroup comes first.
+template <int NW, int U, bool kRouted = false>
+__global__ void __launch_bounds__(NW * 64)
+decode_down_split(const uint16_t *__restrict__ Hin, int ldx, int T, const uint16_t *__restrict__ Wd, int ldw,
+                  int d_model, float *__restrict__ out, const uint8_t *__restrict__ route, BranchTable bt)
+{
+    static_assert(NW >= 4, "the final reduction uses 256 threads");
+    constexpr int RT = 2, KS = 2;
+    __shared__ float red[NW][RT][256];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int r16 = lane & 15, q = lane >> 4;
+    const Stretches<kRouted> st{bt, kRouted ? live_branches(bt, route, T) : 0ULL};
+    const int row0 = blockIdx.x * (16 * RT);
+    const uint16_t *wrow[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        int m = row0 + rt * 16 + r16;
+        m = m < d_model ? m : d_model - 1;               // clamped rows are computed but never stored
+        wrow[rt] = Wd + (size_t)m * ldw + q * 16;
+    }
+    const bool tok = r16 < T;
+    const uint16_t *xp = Hin + (size_t)(tok ? r16 : 0) * ldx + q * 16;
+    const uint16_t *zero = reinterpret_cast<const uint16_t *>(g_zero16);
+
+    // cursor over this wave's blocks: rounds of NW blocks go to the KS workgroups in turn
+    const int n_ranges = st.count();
+    const int first = wave + NW * (int)blockIdx.y, stride = NW * KS;
+    int cr = 0, cb = first;
+    auto settle = [&]() {                                // move past ranges the block index overshoots
+        while (cr < n_ranges) {
+            const int nb = (st.end(cr) - st.beg(cr) + KB - 1) / KB;
+            if (cb < nb) break;
+            cb -= nb;
+            ++cr;
+        }
+    };
+    settle();
+    int total = 0;                                       // blocks of this wave in all ranges
+    {
+        int sk = first;
+        for (int r = 0; r < n_ranges; ++r) {
+            const int nb = (st.end(r) - st.beg(r) + KB - 1) / KB;
+            const int mine = nb > sk ? (nb - sk + stride - 1) / stride : 0;
+            total += mine;
+            sk = sk + mine * stride - nb;
+        }
+    }
+
+    u32x4 wa[U][RT][2], xa[U][2];
+    auto load_block = [&](int u) {                       // loads the block under the cursor, then advances
+        const bool live = cr < n_ranges;
+        const int k = live ? st.beg(cr) + cb * KB : 0;
+        const int kend = live ? st.end(cr) : -1;
+        const int kl = k + q * 16;
+        const bool ok0 = kl < kend, ok1 = kl + 8 < kend;
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+            wa[u][rt][0] = ld16(ok0 ? wrow[rt] + k : zero);
+            wa[u][rt][1] = ld16(ok1 ? wrow[rt] + k + 8 : zero);
+        }
+        xa[u][0] = ld16((ok0 && tok) ? xp + k : zero);
+        xa[u][1] = ld16((ok1 && tok) ? xp + k + 8 : zero);
+        cb += stride;
+        settle();
+    };
+
+    f32x4 acc[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) acc[rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int u = 0; u < U; ++u) load_block(u);
+    for (int j = 0; j < total; j += U) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt) {
+                acc[rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(wa[u][rt][0]), as_bf16x8(xa[u][0]), acc[rt], 0, 0, 0);
+                acc[rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(wa[u][rt][1]), as_bf16x8(xa[u][1]), acc[rt], 0, 0, 0);
+            }
+            load_block(u);                               // past the last block this loads zeros
+        }
+    }
+
+    // cross-wave sum in wave order, then this workgroup's half of K goes into out
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) red[wave][rt][v * 64 + lane] = acc[rt][v];
+    __syncthreads();
+    if (threadIdx.x >= 256) return;
+    const int v = threadIdx.x >> 6;
+    const int row = 4 * q + v;                           // register v of lane l is D[row 4*(l>>4)+v][col l&15]
+    const int t = r16;
+    if (t >= T) return;
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        float s0 = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) s0 += red[w][rt][threadIdx.x];
+        const int m = row0 + rt * 16 + row;
+        if (m < d_model) atomicAdd(&out[(size_t)t * d_model + m], s0);
+    }
+}
+
 // Persistent gate+up kernel for layers whose x fits in LDS (T * (d_model*2 + 16) bytes).
 // One workgroup per CU copies x into LDS once and then walks its tiles (tile t belongs to
 // workgroup t % grid, so every CU gets the same number).  The NW waves of the workgroup share each
@@ -252,8 +364,11 @@ template <int NW, int U, bool kRouted = false>
 __global__ void __launch_bounds__(NW * 64)
 decode_gate_up_persist(const uint16_t *__restrict__ X, int T, const uint16_t *__restrict__ Wg,
                        const uint16_t *__restrict__ Wu, int d_model, uint16_t *__restrict__ Hout, int ldh,
-                       const uint8_t *__restrict__ route, BranchTable bt)
+                       const uint8_t *__restrict__ route, float *__restrict__ clear, int clear_n, BranchTable bt)
 {
+    // clear (may be null): clear_n floats to set to 0 for the kernel that follows (decode_down_split)
+    if (clear)
+        for (int i = blockIdx.x * (NW * 64) + threadIdx.x; i < clear_n; i += gridDim.x * (NW * 64)) clear[i] = 0.f;
     static_assert(NW >= 4, "the reduction uses 256 threads");
     extern __shared__ __attribute__((aligned(16))) char smem[];
     float *red = reinterpret_cast<float *>(smem);                 // [2][NW][256]
@@ -396,6 +511,10 @@ static hipError_t launch_decode_impl(const FwdArgs &a, const BranchTable &bt)
     const uint16_t *X = static_cast<const uint16_t *>(a.x);
     uint16_t *H = static_cast<uint16_t *>(a.H);
     const size_t xs_bytes = (size_t)a.T * (a.d_model * 2 + 16) + 16 + 2 * MLPMOE_DEC_SNW * 256 * sizeof(float);
+    // Layers with many output features take the down kernel that splits K over two workgroups and adds
+    // the halves into `out` with atomics; `out` is cleared by the persistent gate+up kernel, so the
+    // pair is only used together (and for a float result).
+    const bool split_down = tiles2 >= 192 && xs_bytes <= kStreamLdsMax && !a.out_bf16;
     if (xs_bytes <= kStreamLdsMax) {
         // per device, set up on the first call there: CU count and the kernel's LDS limit
         static std::mutex mu;
@@ -423,7 +542,7 @@ static hipError_t launch_decode_impl(const FwdArgs &a, const BranchTable &bt)
         ProfileScope ps(MLPMOE_KERNEL_DECODE_GATE_UP, a.stream);
         decode_gate_up_persist<MLPMOE_DEC_SNW, MLPMOE_DEC_SU, kRouted><<<grid, MLPMOE_DEC_SNW * 64, xs_bytes, a.stream>>>(
             X, a.T, static_cast<const uint16_t *>(a.Wg), static_cast<const uint16_t *>(a.Wu), a.d_model, H,
-            a.ldh, a.route, bt);
+            a.ldh, a.route, split_down ? a.out : nullptr, split_down ? a.T * a.d_model : 0, bt);
         if (launch_status("decode_gate_up_persist launch") != hipSuccess) return hipErrorLaunchFailure;
     } else {
         ProfileScope ps(MLPMOE_KERNEL_DECODE_GATE_UP, a.stream);
@@ -433,7 +552,10 @@ static hipError_t launch_decode_impl(const FwdArgs &a, const BranchTable &bt)
         if (launch_status("decode gate_up launch") != hipSuccess) return hipErrorLaunchFailure;
     }
     ProfileScope ps(MLPMOE_KERNEL_DECODE_DOWN, a.stream);
-    if (tiles2 >= 192)
+    if (split_down)
+        decode_down_split<8, 4, kRouted><<<dim3(ceil_div(a.d_model, 32), 2), 8 * 64, 0, a.stream>>>(
+            H, a.ldh, a.T, static_cast<const uint16_t *>(a.Wd), a.d_inter, a.d_model, a.out, a.route, bt);
+    else if (tiles2 >= 192)
         decode_kernel<MLPMOE_DEC_NW2, MLPMOE_DEC_U2, false, kRouted><<<tiles2, MLPMOE_DEC_NW2 * 64, 0, a.stream>>>(
             H, a.ldh, a.T, static_cast<const uint16_t *>(a.Wd), nullptr, a.d_inter, a.d_model, nullptr,
             a.ldh, a.out, a.out_bf16 ? 1 : 0, a.route, bt);

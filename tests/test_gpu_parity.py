@@ -281,3 +281,28 @@ def test_first_k_sweep(mm, K):
     a1 = (L.x[:1],) + args[1:]
     got = run_gpu(*a1)
     assert oracle.rel_max_err(got, oracle_out(*a1, "exact")) <= BF16_TOL
+
+
+def test_wide_layer_decode_is_reproducible_and_clears_out(mm):
+    """d_model >= 3072: the down projection splits K over two workgroups and adds the halves with float
+    atomics into an `out` the gate+up kernel has cleared.  The bits must not depend on the order of the two
+    atomics (30 repetitions), nor on what `out` held before, and the result must match the oracle."""
+    import torch
+    d_model, d_inter, B = 3072, 1536, 6
+    for T in (1, 11, 16):
+        L = synth.make_layer("qwen05b", T, seed=80 + T, d_model=d_model, d_inter=d_inter, B=B)
+        off, _, mask, _ = mm.mlpmoe_slice(d_inter, B)
+        mask[4] = 0
+        x, Wg, Wu, Wd = (to_dev(a) for a in (L.x, L.W_gate, L.W_up, L.W_down))
+        first = None
+        for rep in range(30):
+            out = torch.full((T, d_model), float("nan") if rep % 2 else 1e30, dtype=torch.float32, device="cuda")
+            mm.mlpmoe_forward_bf16(x, Wg, Wu, Wd, off, L.alpha_draw, mask, out=out)
+            if first is None:
+                first = out.clone()
+            else:
+                assert torch.equal(out, first), rep
+        got = first.cpu().numpy()
+        for mode in ("contract", "exact"):
+            ref = oracle_out(L.x, L.W_gate, L.W_up, L.W_down, off, L.alpha_draw, mask, mode)
+            assert oracle.rel_max_err(got, ref) <= BF16_TOL, (T, mode)

@@ -191,7 +191,7 @@ def others(mm, synth, torch, seed):
     """Short runs of the remaining workloads: tokens/s and the fraction of the roofline that bounds them."""
     res = {}
     for name, Ts in (("qwen05b", (2048, 1)), ("qwen05b_pruned", (2048, 16, 1)), ("llama8b_fade", (4096, 16, 1)),
-                     ("llama8b", (512,))):
+                     ("llama8b", (512, 256, 64))):
         Tmax = max(Ts)
         L, x, dev, _, off, alpha, mask, d_eff = build_layer(mm, synth, name, Tmax, seed)
         w = L.workload
@@ -216,6 +216,9 @@ def others(mm, synth, torch, seed):
                 ent["weight_sets"] = len(sets)
             else:
                 ent["mfma_frac"] = round(6.0 * T * w.d_model * d_eff / (ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS, 4)
+                if T < 512:      # between the two rooflines: the weight stream matters as much as the flops
+                    byts = 3 * w.d_model * d_eff * 2 + T * w.d_model * 6
+                    ent["hbm_frac"] = round(byts / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
             res["%s_T%d" % (name, T)] = ent
             del sets, out
         if name == "llama8b":

@@ -149,12 +149,15 @@ MLPMOE_API size_t mlpmoe_workspace_bytes(int T, int d_model, int d_inter, int B,
  * that uses floating-point atomics (the decode down projection of wide layers) adds exactly two
  * partial sums into a zero, which gives the same number in either order.
  *
- * Workspace: taken from a per-device buffer the library owns and grows with
- * hipMalloc when a call needs more than any earlier one (that growth synchronises
- * the device).  Calls that overlap in time on one device must use the *_ws form
- * with distinct workspaces.
+ * Workspace: the block given to mlpmoe_set_workspace() for the current device if there is
+ * one -- the call then never allocates and returns MLPMOE_ERR_WORKSPACE if the block is too
+ * small.  Otherwise a per-device buffer the library owns and grows with hipMalloc when a call
+ * needs more than any earlier one (that growth synchronises the device; while `stream` is
+ * recording a graph it is refused with MLPMOE_ERR_WORKSPACE instead).  Either way all calls
+ * of this kind on one device share one block: calls that overlap in time on one device
+ * (different streams) must use the *_ws form with distinct workspaces.
  *
- * Errors: NULL, SHAPE, OFFSETS, ALIGN, WORKSPACE (allocation failed), HIP.
+ * Errors: NULL, SHAPE, OFFSETS, ALIGN, WORKSPACE (too small / allocation failed), HIP.
  */
 MLPMOE_API int mlpmoe_forward_bf16(const void *x, const void *W_gate, const void *W_up, const void *W_down,
                         const int32_t *branch_offsets, const float *alpha,
@@ -194,6 +197,27 @@ MLPMOE_API int mlpmoe_forward_bf16_out_bf16_ws(const void *x, const void *W_gate
                                     const uint8_t *active_mask, int T, int d_model, int d_inter, int B,
                                     void *out, void *workspace, size_t workspace_bytes, int path,
                                     void *stream);
+
+/*
+ * mlpmoe_set_workspace -- gives the entry points that take no workspace argument (mlpmoe_forward,
+ * mlpmoe_forward_bf16, mlpmoe_forward_f32, mlpmoe_forward_bf16_out_bf16, mlpmoe_forward_routed_*)
+ * a caller-owned device block to work in on the CURRENT device, e.g. a PyTorch tensor.  From then
+ * on those calls allocate nothing and synchronise nothing on that device: a call that needs more
+ * than `bytes` (mlpmoe_workspace_bytes) returns MLPMOE_ERR_WORKSPACE.  dev_ptr: device, 256-byte
+ * aligned, owned by the caller, who keeps it alive until it is replaced or cleared and all work
+ * enqueued with it has finished; its contents are scratch.  dev_ptr == NULL clears the setting
+ * (back to the library-owned buffer).  Errors: WORKSPACE (misaligned, or bytes == 0), HIP.
+ */
+MLPMOE_API int mlpmoe_set_workspace(void *dev_ptr, size_t bytes);
+
+/*
+ * Layout of a workspace while and after a bf16 forward runs in it: it begins with the gated
+ * intermediate of Sec. 3.1's bracket, H[t][j] = bf16(alpha_b SiLU(g) u), row-major [T, ld] with
+ * ld = mlpmoe_hidden_ld(d_inter) (d_inter rounded up to a multiple of 64; 0 for d_inter < 0) and
+ * column j = neuron j of the weight buffers.  Columns of inactive branches are never written.
+ * For tests and debugging; float storage keeps H as float with the same ld.
+ */
+MLPMOE_API int mlpmoe_hidden_ld(int d_inter);
 
 /*
  * Caller-owned workspace forms.  workspace: device pointer, 256-byte aligned, at

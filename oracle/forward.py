@@ -41,6 +41,8 @@ def _load():
         lib.oracle_mlpmoe_forward.restype = ctypes.c_int
         lib.oracle_mlpmoe_forward_routed.argtypes = [fp, fp, fp, fp, ip, fp, bp, bp] + [ctypes.c_int] * 5 + [dp]
         lib.oracle_mlpmoe_forward_routed.restype = ctypes.c_int
+        lib.oracle_mlpmoe_hidden.argtypes = [fp, fp, fp, ip, fp, bp] + [ctypes.c_int] * 5 + [dp] * 5
+        lib.oracle_mlpmoe_hidden.restype = ctypes.c_int
         lib.oracle_dense_swiglu.argtypes = [fp, fp, fp, fp] + [ctypes.c_int] * 3 + [dp]
         lib.oracle_dense_swiglu.restype = ctypes.c_int
         lib.oracle_num_threads.restype = ctypes.c_int
@@ -116,6 +118,34 @@ def mlpmoe_forward_routed(x, W_gate, W_up, W_down, branch_offsets, alpha, active
     if rc != 0:
         raise ValueError("oracle_mlpmoe_forward_routed rejected its arguments (rc=%d)" % rc)
     return out
+
+
+def mlpmoe_hidden(x, W_gate, W_up, branch_offsets, alpha, active_mask, mode="exact", details=False):
+    """The gated intermediate alpha_b * SiLU(W_gate x) * W_up x of Sec. 3.1's bracket, [T, d_inter] fp64
+    (0 for neurons of inactive branches).  mode "contract": formed in float and rounded once to bf16.
+    details=True also returns (g, u, abs_g, abs_u): the two dot products and the sums of the
+    absolute values of their terms."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    T, d_model = x.shape
+    off = np.ascontiguousarray(branch_offsets, dtype=np.int32)
+    B = off.shape[0] - 1
+    d_inter = int(off[-1])
+    Wg = _f32(W_gate, (d_inter, d_model))
+    Wu = _f32(W_up, (d_inter, d_model))
+    al = _f32(alpha, (B,))
+    mk = np.ascontiguousarray(active_mask, dtype=np.uint8)
+    if mk.shape != (B,):
+        raise ValueError("active_mask must have B entries")
+    h = np.empty((T, d_inter), dtype=np.float64)
+    extra = [np.empty((T, d_inter), dtype=np.float64) for _ in range(4)] if details else [None] * 4
+    m = {"exact": 0, "contract": 1}[mode]
+    rc = _load().oracle_mlpmoe_hidden(_ptr(x, ctypes.c_float), _ptr(Wg, ctypes.c_float), _ptr(Wu, ctypes.c_float),
+                                      _ptr(off, ctypes.c_int32), _ptr(al, ctypes.c_float), _ptr(mk, ctypes.c_uint8),
+                                      T, d_model, d_inter, B, m, _ptr(h, ctypes.c_double),
+                                      *[None if e is None else _ptr(e, ctypes.c_double) for e in extra])
+    if rc != 0:
+        raise ValueError("oracle_mlpmoe_hidden rejected its arguments (rc=%d)" % rc)
+    return (h, *extra) if details else h
 
 
 def dense_swiglu(x, W_gate, W_up, W_down):

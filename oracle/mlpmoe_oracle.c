@@ -171,6 +171,68 @@ int oracle_mlpmoe_forward_routed(const float *x, const float *Wg, const float *W
     return fail ? -2 : 0;
 }
 
+/*
+ * The gated intermediate on its own (the bracket of Sec. 3.1 times alpha_b), for tests that look at
+ * the bf16 pipeline's single rounding point directly instead of through the down projection:
+ *     h[t][j] = alpha_b * SiLU(g) * u,   g = <W_gate[j], x_t>,  u = <W_up[j], x_t>,  b = branch of j
+ * mode 0: that product in double.  mode 1: formed in float and rounded once to bf16, exactly as the
+ * contract mode of oracle_mlpmoe_forward does (so that forward(contract) = h(contract) W_down^T).
+ * Neurons of inactive branches get 0.  Optional outputs (NULL to skip), each [T, d_inter]:
+ *     g, u          the two dot products in double
+ *     abs_g, abs_u  sum_k |x_k| |w_k| of the same dot products: the scale of the rounding error of
+ *                   any floating-point evaluation of them, which decides how close to a bf16
+ *                   rounding boundary a value must lie before two correct evaluations may round it
+ *                   to different neighbours.
+ */
+int oracle_mlpmoe_hidden(const float *x, const float *Wg, const float *Wu, const int32_t *off,
+                         const float *alpha, const uint8_t *active, int T, int d_model, int d_inter, int B,
+                         int mode, double *h, double *g_out, double *u_out, double *abs_g, double *abs_u)
+{
+    if (!x || !Wg || !Wu || !off || !alpha || !active || !h) return -1;
+    if (T < 0 || d_model <= 0 || d_inter < 0 || B <= 0) return -1;
+    if (off[0] != 0 || off[B] != d_inter) return -1;
+    for (int b = 0; b < B; ++b)
+        if (off[b + 1] < off[b]) return -1;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int t = 0; t < T; ++t) {
+        const float *x_row = x + (size_t)t * d_model;
+        for (int b = 0; b < B; ++b) {
+            for (int j = off[b]; j < off[b + 1]; ++j) {
+                const size_t o = (size_t)t * d_inter + j;
+                const float *g_row = Wg + (size_t)j * d_model;
+                const float *u_row = Wu + (size_t)j * d_model;
+                double g = 0.0, u = 0.0, ag = 0.0, au = 0.0;
+                if (active[b]) {
+                    for (int k = 0; k < d_model; ++k) {
+                        const double pg = (double)x_row[k] * (double)g_row[k];
+                        const double pu = (double)x_row[k] * (double)u_row[k];
+                        g += pg;
+                        u += pu;
+                        ag += fabs(pg);
+                        au += fabs(pu);
+                    }
+                }
+                double hv = 0.0;
+                if (active[b]) {
+                    if (mode == 0) {
+                        hv = (double)alpha[b] * (silu_d(g) * u);
+                    } else {
+                        float gf = (float)g, uf = (float)u;
+                        float s = gf / (1.0f + expf(-gf));
+                        hv = (double)round_to_bf16(alpha[b] * (s * uf));
+                    }
+                }
+                h[o] = hv;
+                if (g_out) g_out[o] = g;
+                if (u_out) u_out[o] = u;
+                if (abs_g) abs_g[o] = ag;
+                if (abs_u) abs_u[o] = au;
+            }
+        }
+    }
+    return 0;
+}
+
 /* Dense SwiGLU MLP with no branch structure: W_down [ SiLU(W_gate x) (.) W_up x ]  (Sec. 2.2 identity,
  * right-hand side before slicing).  Kept separate from the branched code path on purpose. */
 int oracle_dense_swiglu(const float *x, const float *Wg, const float *Wu, const float *Wd,

@@ -28,7 +28,7 @@ EXPORTS = ["mlpmoe_status_string", "mlpmoe_last_error_detail", "mlpmoe_slice", "
            "mlpmoe_profile_collect", "mlpmoe_profile_disable", "mlpmoe_plan_create", "mlpmoe_plan_forward",
            "mlpmoe_plan_destroy", "mlpmoe_forward_routed_bf16", "mlpmoe_forward_routed_bf16_ws",
            "mlpmoe_forward_bf16_out_bf16", "mlpmoe_forward_bf16_out_bf16_ws",
-           "mlpmoe_forward_routed_f32", "mlpmoe_forward_routed_f32_ws"]
+           "mlpmoe_forward_routed_f32", "mlpmoe_forward_routed_f32_ws", "mlpmoe_set_workspace", "mlpmoe_hidden_ld"]
 
 
 class MlpMoeError(RuntimeError):
@@ -97,6 +97,10 @@ def _load() -> ctypes.CDLL:
     lib.mlpmoe_forward_f32_ws.restype = i
     lib.mlpmoe_release.argtypes = []
     lib.mlpmoe_release.restype = i
+    lib.mlpmoe_set_workspace.argtypes = [vp, sz]
+    lib.mlpmoe_set_workspace.restype = i
+    lib.mlpmoe_hidden_ld.argtypes = [i]
+    lib.mlpmoe_hidden_ld.restype = i
     lib.mlpmoe_profile_enable.argtypes = [i]
     lib.mlpmoe_profile_enable.restype = i
     lib.mlpmoe_profile_collect.argtypes = [vp, vp, i]
@@ -297,6 +301,21 @@ def mlpmoe_release():
     _check(lib.mlpmoe_release(), "mlpmoe_release")
 
 
+def mlpmoe_set_workspace(workspace):
+    """Caller-owned workspace (a torch byte tensor on the current device) for the entry points that take none;
+    None clears it.  The caller keeps the tensor alive while it is set."""
+    if workspace is None:
+        _check(lib.mlpmoe_set_workspace(None, 0), "mlpmoe_set_workspace")
+    else:
+        _check(lib.mlpmoe_set_workspace(_dev_ptr(workspace), int(workspace.numel() * workspace.element_size())),
+               "mlpmoe_set_workspace")
+
+
+def mlpmoe_hidden_ld(d_inter: int) -> int:
+    """Leading dimension of the gated intermediate H at the start of a workspace."""
+    return int(lib.mlpmoe_hidden_ld(int(d_inter)))
+
+
 def mlpmoe_forward_routed_f32(x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, route, out=None,
                               workspace=None, stream=None):
     """The routed forward for float32 x and weights."""
@@ -355,6 +374,11 @@ class Plan:
             _check(lib.mlpmoe_plan_destroy(h), "mlpmoe_plan_destroy")
 
     def __del__(self):
+        # At interpreter shutdown the HIP runtime may already be tearing down: leave the block to the
+        # process exit rather than calling into the runtime from a finaliser.
+        import sys
+        if sys is None or sys.is_finalizing():
+            return
         try:
             self.destroy()
         except Exception:

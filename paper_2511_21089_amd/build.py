@@ -19,14 +19,12 @@ SOURCES = ["mlpmoe_api.cpp", "kernels_generic.hip", "kernels_mfma.hip", "kernels
            "kernels_fade.hip"]
 HEADERS = [os.path.join(CSRC, "internal.h"), os.path.join(ROOT, "include", "mlpmoe.h")]
 
-HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+HIPCC = "/opt/rocm/bin/hipcc"
 # packed fp32 VALU instructions are switched off for device code: the compiler would otherwise form them
 # from ordinary float arithmetic, and some of their forms have given wrong results on this hardware
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
           "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-Wall", "-Wno-unused-function"]
-# extra compiler flags for tuning experiments (e.g. -DMLPMOE_MFMA_WM=2); empty in normal builds
-COMMON += os.environ.get("MLPMOE_HIPCC_FLAGS", "").split()
 
 
 def _compile(src: str) -> str:

@@ -478,25 +478,8 @@ decode_gate_up_persist(const uint16_t *__restrict__ X, int T, const uint16_t *__
     }
 }
 
-#ifndef MLPMOE_DEC_NW1
-#define MLPMOE_DEC_NW1 4
-#endif
-#ifndef MLPMOE_DEC_U1
-#define MLPMOE_DEC_U1 8
-#endif
-#ifndef MLPMOE_DEC_NW2
-#define MLPMOE_DEC_NW2 8
-#endif
-#ifndef MLPMOE_DEC_U2
-#define MLPMOE_DEC_U2 8
-#endif
-
-#ifndef MLPMOE_DEC_SNW
-#define MLPMOE_DEC_SNW 8
-#endif
-#ifndef MLPMOE_DEC_SU
-#define MLPMOE_DEC_SU 8
-#endif
+// waves and ring depth of the instantiations in use: gate+up fallback, down, persistent gate+up
+constexpr int DEC_NW1 = 4, DEC_U1 = 8, DEC_NW2 = 8, DEC_U2 = 8, DEC_SNW = 8, DEC_SU = 8;
 constexpr size_t kStreamLdsMax = 160 * 1024;
 
 }  // namespace
@@ -510,7 +493,7 @@ static hipError_t launch_decode_impl(const FwdArgs &a, const BranchTable &bt)
     if (tiles1 > 0x7fffffffLL) return hipErrorInvalidValue;
     const uint16_t *X = static_cast<const uint16_t *>(a.x);
     uint16_t *H = static_cast<uint16_t *>(a.H);
-    const size_t xs_bytes = (size_t)a.T * (a.d_model * 2 + 16) + 16 + 2 * MLPMOE_DEC_SNW * 256 * sizeof(float);
+    const size_t xs_bytes = (size_t)a.T * (a.d_model * 2 + 16) + 16 + 2 * DEC_SNW * 256 * sizeof(float);
     // Layers with many output features take the down kernel that splits K over two workgroups and adds
     // the halves into `out` with atomics; `out` is cleared by the persistent gate+up kernel, so the
     // pair is only used together (and for a float result).
@@ -531,7 +514,7 @@ static hipError_t launch_decode_impl(const FwdArgs &a, const BranchTable &bt)
                 e = hipGetDeviceProperties(&prop, dev);
                 if (e != hipSuccess) return note_hip_error("hipGetDeviceProperties", e);
                 e = hipFuncSetAttribute(
-                    reinterpret_cast<const void *>(&decode_gate_up_persist<MLPMOE_DEC_SNW, MLPMOE_DEC_SU, kRouted>),
+                    reinterpret_cast<const void *>(&decode_gate_up_persist<DEC_SNW, DEC_SU, kRouted>),
                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kStreamLdsMax);
                 if (e != hipSuccess) return note_hip_error("hipFuncSetAttribute(decode_gate_up_persist)", e);
                 cus_of[dev] = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 1;
@@ -540,13 +523,13 @@ static hipError_t launch_decode_impl(const FwdArgs &a, const BranchTable &bt)
         }
         const int grid = tiles1 < n_cus ? (int)tiles1 : n_cus;
         ProfileScope ps(MLPMOE_KERNEL_DECODE_GATE_UP, a.stream);
-        decode_gate_up_persist<MLPMOE_DEC_SNW, MLPMOE_DEC_SU, kRouted><<<grid, MLPMOE_DEC_SNW * 64, xs_bytes, a.stream>>>(
+        decode_gate_up_persist<DEC_SNW, DEC_SU, kRouted><<<grid, DEC_SNW * 64, xs_bytes, a.stream>>>(
             X, a.T, static_cast<const uint16_t *>(a.Wg), static_cast<const uint16_t *>(a.Wu), a.d_model, H,
             a.ldh, a.route, split_down ? a.out : nullptr, split_down ? a.T * a.d_model : 0, bt);
         if (launch_status("decode_gate_up_persist launch") != hipSuccess) return hipErrorLaunchFailure;
     } else {
         ProfileScope ps(MLPMOE_KERNEL_DECODE_GATE_UP, a.stream);
-        decode_kernel<MLPMOE_DEC_NW1, MLPMOE_DEC_U1, true, kRouted><<<(unsigned)tiles1, MLPMOE_DEC_NW1 * 64, 0, a.stream>>>(
+        decode_kernel<DEC_NW1, DEC_U1, true, kRouted><<<(unsigned)tiles1, DEC_NW1 * 64, 0, a.stream>>>(
             X, a.d_model, a.T, static_cast<const uint16_t *>(a.Wg), static_cast<const uint16_t *>(a.Wu),
             a.d_model, a.d_model, H, a.ldh, nullptr, 0, a.route, bt);
         if (launch_status("decode gate_up launch") != hipSuccess) return hipErrorLaunchFailure;
@@ -556,7 +539,7 @@ static hipError_t launch_decode_impl(const FwdArgs &a, const BranchTable &bt)
         decode_down_split<8, 4, kRouted><<<dim3(ceil_div(a.d_model, 32), 2), 8 * 64, 0, a.stream>>>(
             H, a.ldh, a.T, static_cast<const uint16_t *>(a.Wd), a.d_inter, a.d_model, a.out, a.route, bt);
     else if (tiles2 >= 192)
-        decode_kernel<MLPMOE_DEC_NW2, MLPMOE_DEC_U2, false, kRouted><<<tiles2, MLPMOE_DEC_NW2 * 64, 0, a.stream>>>(
+        decode_kernel<DEC_NW2, DEC_U2, false, kRouted><<<tiles2, DEC_NW2 * 64, 0, a.stream>>>(
             H, a.ldh, a.T, static_cast<const uint16_t *>(a.Wd), nullptr, a.d_inter, a.d_model, nullptr,
             a.ldh, a.out, a.out_bf16 ? 1 : 0, a.route, bt);
     else

@@ -30,10 +30,7 @@ constexpr int BK = 64;           // K elements per tile: one tile row is 128 byt
 constexpr int PART_BYTES = 256 * BK * 2;             // 32768: the A rows, or the 128 + 128 B rows, of one K tile
 constexpr int N_PARTS = 5;                           // ring of parts: A0 B0 A1 B1 A2 | B2 A3 ...
 constexpr int LDS_BYTES = N_PARTS * PART_BYTES;      // 163840: the whole LDS of a CU
-#ifndef MLPMOE_MFMA_WM
-#define MLPMOE_MFMA_WM 4
-#endif
-constexpr int MFMA_WM = MLPMOE_MFMA_WM;              // waves along M: 2 (4 waves) or 4 (8 waves)
+constexpr int MFMA_WM = 4;                           // waves along M: 8 waves of 64 x (64+64) outputs
 
 // 16 zero bytes: K chunks that fall past the end of a range are fetched from here.
 __device__ const uint32_t g_zero_chunk[4] = {0, 0, 0, 0};

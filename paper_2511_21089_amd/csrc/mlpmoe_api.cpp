@@ -18,9 +18,14 @@ using namespace mlpmoe;
 namespace {
 
 struct DeviceWorkspace {
-    void *ptr = nullptr;
+    void *ptr = nullptr;          // library-owned block (hipMalloc), grown on demand
     size_t bytes = 0;
+    void *user_ptr = nullptr;     // caller's block (mlpmoe_set_workspace); when set, nothing is ever allocated
+    size_t user_bytes = 0;
 };
+// Guards g_ws and, for the entry points without a workspace argument, stays locked from the moment
+// the block is chosen until the kernels that use it are enqueued: a growth on another thread
+// synchronises the device before it frees, so work already enqueued is never left with a freed block.
 std::mutex g_ws_mutex;
 std::map<int, DeviceWorkspace> g_ws;
 
@@ -41,9 +46,11 @@ int validate_common(const void *x, const void *Wg, const void *Wu, const void *W
     if (!off || !alpha || !mask) return MLPMOE_ERR_NULL;
     if (B < 1 || B > MLPMOE_MAX_BRANCHES || T < 0 || d_model < 1 || d_inter < 0)
         return MLPMOE_ERR_SHAPE;
-    // index arithmetic inside the kernels is 32-bit for rows and columns, 64-bit for addresses
+    // index arithmetic inside the kernels is 32-bit for rows and columns, 64-bit for addresses; byte
+    // offsets of a row inside a 256-row tile (row * leading dimension * 2) are 32-bit unsigned, which
+    // bounds the leading dimensions d_model and d_inter (+63 for the intermediate) by 2^22
     if ((long long)T * d_model > (1LL << 40) || (long long)d_inter * d_model > (1LL << 40) ||
-        d_model > (1 << 24) || d_inter > (1 << 24) || T > (1 << 24))
+        d_model > (1 << 22) || d_inter > (1 << 22) || T > (1 << 24))
         return MLPMOE_ERR_SHAPE;
     if (off[0] != 0) return MLPMOE_ERR_OFFSETS;
     for (int b = 0; b < B; ++b)
@@ -172,8 +179,9 @@ int forward_impl(const void *x, const void *Wg, const void *Wu, const void *Wd, 
                          path, is_bf16, stream, nullptr, out_bf16);
 }
 
-// Library-owned workspace of the current device, grown on demand.
-int owned_workspace(size_t need, void **ptr, size_t *bytes)
+// Workspace of the current device for the entry points that take none: the caller's block if one
+// was set, else the library-owned one, grown on demand.  g_ws_mutex must be held by the caller.
+int owned_workspace(size_t need, hipStream_t stream, void **ptr, size_t *bytes)
 {
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
@@ -181,9 +189,18 @@ int owned_workspace(size_t need, void **ptr, size_t *bytes)
         (void)note_hip_error("hipGetDevice", e);
         return MLPMOE_ERR_HIP;
     }
-    std::lock_guard<std::mutex> lock(g_ws_mutex);
     DeviceWorkspace &w = g_ws[dev];
+    if (w.user_ptr) {                        // caller-owned: use it or refuse, never allocate
+        if (w.user_bytes < need) return MLPMOE_ERR_WORKSPACE;
+        *ptr = w.user_ptr;
+        *bytes = w.user_bytes;
+        return MLPMOE_OK;
+    }
     if (w.bytes < need) {
+        // growing synchronises the device and allocates: neither is allowed while the stream records a graph
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(stream, &cap) != hipSuccess) (void)hipGetLastError();
+        if (cap != hipStreamCaptureStatusNone) return MLPMOE_ERR_WORKSPACE;
         if (w.ptr) {
             e = hipDeviceSynchronize();      // earlier launches may still be using the old block
             if (e != hipSuccess) {
@@ -217,7 +234,8 @@ int forward_owned(const void *x, const void *Wg, const void *Wu, const void *Wd,
     size_t need = mlpmoe_workspace_bytes(T, d_model, d_inter, B, is_bf16 ? 2 : 4);
     void *ws = nullptr;
     size_t ws_bytes = 0;
-    rc = owned_workspace(need, &ws, &ws_bytes);
+    std::lock_guard<std::mutex> lock(g_ws_mutex);      // held until the kernels are enqueued
+    rc = owned_workspace(need, stream, &ws, &ws_bytes);
     if (rc != MLPMOE_OK) return rc;
     return forward_impl(x, Wg, Wu, Wd, off, alpha, mask, T, d_model, d_inter, B, out, ws, ws_bytes,
                         MLPMOE_PATH_AUTO, is_bf16, stream, out_bf16);
@@ -481,6 +499,24 @@ size_t mlpmoe_workspace_bytes(int T, int d_model, int d_inter, int B, int elem_b
     return bytes + 256 + route_scratch_bytes(T, d_inter);     // slack, then the routed path's tile tables
 }
 
+int mlpmoe_set_workspace(void *dev_ptr, size_t bytes)
+{
+    if (dev_ptr && ((reinterpret_cast<uintptr_t>(dev_ptr) & 255u) || bytes == 0)) return MLPMOE_ERR_WORKSPACE;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) {
+        (void)note_hip_error("hipGetDevice", e);
+        return MLPMOE_ERR_HIP;
+    }
+    std::lock_guard<std::mutex> lock(g_ws_mutex);
+    DeviceWorkspace &w = g_ws[dev];
+    w.user_ptr = dev_ptr;
+    w.user_bytes = dev_ptr ? bytes : 0;
+    return MLPMOE_OK;
+}
+
+int mlpmoe_hidden_ld(int d_inter) { return d_inter < 0 ? 0 : h_ld(d_inter); }
+
 int mlpmoe_forward_bf16_ws(const void *x, const void *W_gate, const void *W_up, const void *W_down,
                            const int32_t *branch_offsets, const float *alpha,
                            const uint8_t *active_mask, int T, int d_model, int d_inter, int B,
@@ -553,8 +589,10 @@ static int forward_routed(const void *x, const void *Wg, const void *Wu, const v
     if (rc != MLPMOE_OK) return rc;
     if (T == 0) return MLPMOE_OK;
     if (!route) return MLPMOE_ERR_NULL;
+    std::unique_lock<std::mutex> lock(g_ws_mutex, std::defer_lock);
     if (own) {
-        rc = owned_workspace(mlpmoe_workspace_bytes(T, d_model, d_inter, B, is_bf16 ? 2 : 4), &workspace,
+        lock.lock();                                   // held until the kernels are enqueued
+        rc = owned_workspace(mlpmoe_workspace_bytes(T, d_model, d_inter, B, is_bf16 ? 2 : 4), stream, &workspace,
                              &workspace_bytes);
         if (rc != MLPMOE_OK) return rc;
     }

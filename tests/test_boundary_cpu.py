@@ -112,6 +112,21 @@ def test_workspace_bytes():
     assert a >= 4096 * 14336 * 2
 
 
+def test_set_workspace_validation_and_hidden_ld():
+    f = mm.lib.mlpmoe_set_workspace
+    assert f(ctypes.c_void_p(0x1010), 4096) == mm.ERR_WORKSPACE      # not 256-byte aligned
+    assert f(ctypes.c_void_p(0x1000), 0) == mm.ERR_WORKSPACE         # a block of no bytes
+    assert mm.mlpmoe_hidden_ld(4864) == 4864 and mm.mlpmoe_hidden_ld(4870) == 4928
+    assert mm.mlpmoe_hidden_ld(0) == 64 and mm.mlpmoe_hidden_ld(-1) == 0
+    # leading dimensions beyond what the kernels' 32-bit row offsets hold are refused up front
+    off = np.array([0, (1 << 22) + 8], np.int32)
+    al = np.ones(1, np.float32)
+    mk = np.ones(1, np.uint8)
+    vp = ctypes.c_void_p
+    assert mm.lib.mlpmoe_forward_bf16(vp(0x1000), vp(0x1000), vp(0x1000), vp(0x1000), off.ctypes.data, al.ctypes.data,
+                                      mk.ctypes.data, 4, 64, (1 << 22) + 8, 1, vp(0x1000), None) == mm.ERR_SHAPE
+
+
 def _fwd_args(off, al, mk, T=4, d_model=64, d_inter=256, B=4, x=0x1000, w=0x1000, out=0x1000):
     vp = ctypes.c_void_p
     return [vp(x), vp(w), vp(w), vp(w), off.ctypes.data, al.ctypes.data, mk.ctypes.data, T, d_model,

@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 
 import oracle
-from gpu_util import BF16_TOL, FP32_TOL, oracle_out, run_gpu, to_dev
+from gpu_util import BF16_TOL, FP32_TOL, check_bf16_flip_aware, oracle_out, run_gpu, run_gpu_with_hidden, to_dev
 from paper_2511_21089_amd import synth
 
 pytestmark = pytest.mark.gpu
@@ -275,12 +275,36 @@ def test_first_k_sweep(mm, K):
     args = (L.x, L.W_gate, L.W_up, L.W_down, off, alpha, mask)
     if K * 608 >= 1000:                                    # see check_bf16: enough active neurons
         check_bf16(run_gpu(*args), args)
-    else:
-        got = run_gpu(*args)
-        assert oracle.rel_max_err(got, oracle_out(*args, "exact")) <= BF16_TOL
+    got, H = run_gpu_with_hidden(*args)                    # any K: H itself and both oracle modes, flips accounted for
+    check_bf16_flip_aware(got, H, *args, label="first-K K=%d T=64:" % K)
+    assert np.array_equal(got, run_gpu(*args))
     a1 = (L.x[:1],) + args[1:]
-    got = run_gpu(*a1)
-    assert oracle.rel_max_err(got, oracle_out(*a1, "exact")) <= BF16_TOL
+    got, H = run_gpu_with_hidden(*a1)
+    check_bf16_flip_aware(got, H, *a1, label="first-K K=%d T=1:" % K)
+
+
+THIN_CASES = [
+    # active neurons from 8 to 512: one thin branch of a faded or pruned layer.  T, d_model, offsets, mask
+    (300, 136, [0, 8], [1]),
+    (300, 256, [0, 64, 128, 136], [0, 1, 1]),              # 72 active
+    (257, 264, [0, 200, 456, 1000], [1, 0, 0]),            # 200 active, run ends mid tile
+    (64, 512, [0, 384], [1]),                              # the shape of the first failure of a plain 1e-2 gate
+    (600, 128, [0, 256, 512, 768], [1, 1, 0]),             # 512 active, three token tiles, K split
+    (16, 136, [0, 8, 16, 48], [1, 0, 1]),                  # decode-sized batches on every path
+    (3, 512, [0, 384], [1]),
+]
+
+
+@pytest.mark.parametrize("T,dm,off,mask", THIN_CASES)
+def test_bf16_thin_layers_every_path(mm, T, dm, off, mask):
+    """Layers with 8 .. 512 active neurons in contract AND exact mode on the generic, MFMA and decode kernels:
+    the stored intermediate is compared element by element, and the outputs with the flips accounted for."""
+    args = small_bf16_case(500 + T + dm, T, dm, off, mask)
+    paths = [mm.PATH_GENERIC, mm.PATH_MFMA] + ([mm.PATH_DECODE] if T <= 16 else [])
+    for p in paths:
+        got, H = run_gpu_with_hidden(*args, path=p)
+        check_bf16_flip_aware(got, H, *args, label="thin T=%d d_model=%d path=%d:" % (T, dm, p))
+    assert np.array_equal(run_gpu(*args), run_gpu_with_hidden(*args, path=mm.PATH_AUTO)[0])
 
 
 def test_wide_layer_decode_is_reproducible_and_clears_out(mm):

@@ -133,11 +133,25 @@ def test_routed_full_size(mm):
                                         workspace=ws).cpu().numpy()
     assert np.all(np.isfinite(got))
     host = (widen(L.x), widen(L.W_gate), widen(L.W_up), widen(L.W_down))
-    for mode in ("contract", "exact"):
-        ref = oracle.mlpmoe_forward_routed(*host, off, alpha, mask, route, mode=mode)
-        err = oracle.rel_max_err(got, ref)
-        print("routed full size err(%s) = %.2e" % (mode, err), flush=True)
-        assert err <= BF16_TOL, (mode, err)
+    ref_c = oracle.mlpmoe_forward_routed(*host, off, alpha, mask, route, mode="contract")
+    ref_e = oracle.mlpmoe_forward_routed(*host, off, alpha, mask, route, mode="exact")
+    e_c, e_e = oracle.rel_max_err(got, ref_c), oracle.rel_max_err(got, ref_e)
+    e_ce = oracle.rel_max_err(ref_c, ref_e)
+    print("routed full size err(contract) = %.2e err(exact) = %.2e; contract oracle vs exact oracle %.2e"
+          % (e_c, e_e, e_ce), flush=True)
+    assert e_c <= BF16_TOL, e_c
+    # Every token takes a quarter of the neurons here and the maximum runs over 16.7 million outputs: the one
+    # bf16 rounding of H alone puts the CONTRACT ORACLE about 1e-2 of rms away from the exact one on the worst
+    # element (seed dependent, printed above), so against the exact oracle the kernels can only be asked to
+    # be no further away than that rounding puts them
+    assert e_e <= e_ce + e_c + 1e-4, (e_e, e_ce, e_c)
+    # ... and, on one token row per 16-row fragment, the per-element bounds with H read back
+    rows = np.array([16 * i + (5 * i) % 16 for i in range(256)])
+    ld = mm.mlpmoe_hidden_ld(14336)
+    Hb = ws[: 4096 * ld * 2].view(torch.int16).view(4096, ld)[torch.from_numpy(rows).cuda()][:, :14336]
+    H = synth.bf16_bits_to_f32(Hb.cpu().numpy().view(np.uint16)).astype(np.float64)
+    check_bf16_flip_aware(got[rows], H, L.x[rows], L.W_gate, L.W_up, L.W_down, off, alpha, mask, route=route[rows],
+                          label="routed full size, 256 sampled rows:")
 
 
 def test_tile_list_ragged_groups_uneven_branches_unaligned_route(mm):

@@ -199,6 +199,27 @@ MLPMOE_API int mlpmoe_forward_bf16_out_bf16_ws(const void *x, const void *W_gate
                                     void *stream);
 
 /*
+ * mlpmoe_forward_bf16_noalloc -- mlpmoe_forward_bf16 for callers that cannot allocate device memory
+ * and have no workspace to hand over: code recorded into a HIP graph, tight serving loops, harnesses
+ * that forbid allocation.  Same arguments, arithmetic, kernels and results (bit for bit) as
+ * mlpmoe_forward_bf16_ws with MLPMOE_PATH_AUTO; the workspace is a fixed block of
+ * MLPMOE_NOALLOC_SCRATCH_BYTES that is part of the library's device image (every GPU the library runs
+ * on holds its own copy from the moment the code is loaded until the process ends).  The call
+ * allocates and frees nothing and synchronises nothing.  The first call on a device looks the block's
+ * address up (once per device); make that call outside a graph capture.
+ * Limit: mlpmoe_workspace_bytes(T, d_model, d_inter, B, 2) <= MLPMOE_NOALLOC_SCRATCH_BYTES (all decode
+ * sizes T <= 16 of layers up to d_inter = 262144; prefill of small layers), otherwise
+ * MLPMOE_ERR_WORKSPACE and nothing is enqueued (mlpmoe_last_error_detail() says how much was needed).
+ * All calls on one GPU share that GPU's block, which keeps the last call's contents (nothing in it has
+ * to start at zero: every value a kernel reads from it was written by the same call): calls that
+ * overlap in time on one GPU (different streams) race on it and must not be made.
+ */
+#define MLPMOE_NOALLOC_SCRATCH_BYTES (16u << 20)
+MLPMOE_API int mlpmoe_forward_bf16_noalloc(const void *x, const void *W_gate, const void *W_up, const void *W_down,
+                                const int32_t *branch_offsets, const float *alpha, const uint8_t *active_mask,
+                                int T, int d_model, int d_inter, int B, float *out, void *stream);
+
+/*
  * mlpmoe_set_workspace -- gives the entry points that take no workspace argument (mlpmoe_forward,
  * mlpmoe_forward_bf16, mlpmoe_forward_f32, mlpmoe_forward_bf16_out_bf16, mlpmoe_forward_routed_*)
  * a caller-owned device block to work in on the CURRENT device, e.g. a PyTorch tensor.  From then

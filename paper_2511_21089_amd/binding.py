@@ -28,7 +28,8 @@ EXPORTS = ["mlpmoe_status_string", "mlpmoe_last_error_detail", "mlpmoe_slice", "
            "mlpmoe_profile_collect", "mlpmoe_profile_disable", "mlpmoe_plan_create", "mlpmoe_plan_forward",
            "mlpmoe_plan_destroy", "mlpmoe_forward_routed_bf16", "mlpmoe_forward_routed_bf16_ws",
            "mlpmoe_forward_bf16_out_bf16", "mlpmoe_forward_bf16_out_bf16_ws",
-           "mlpmoe_forward_routed_f32", "mlpmoe_forward_routed_f32_ws", "mlpmoe_set_workspace", "mlpmoe_hidden_ld"]
+           "mlpmoe_forward_routed_f32", "mlpmoe_forward_routed_f32_ws", "mlpmoe_set_workspace", "mlpmoe_hidden_ld",
+           "mlpmoe_forward_bf16_noalloc"]
 
 
 class MlpMoeError(RuntimeError):
@@ -84,7 +85,7 @@ def _load() -> ctypes.CDLL:
     lib.mlpmoe_workspace_bytes.argtypes = [i, i, i, i, i]
     lib.mlpmoe_workspace_bytes.restype = sz
     fwd = [vp, vp, vp, vp, ip, fp, bp, i, i, i, i, vp, vp]
-    for name in ("mlpmoe_forward_bf16", "mlpmoe_forward", "mlpmoe_forward_f32"):
+    for name in ("mlpmoe_forward_bf16", "mlpmoe_forward", "mlpmoe_forward_f32", "mlpmoe_forward_bf16_noalloc"):
         getattr(lib, name).argtypes = fwd
         getattr(lib, name).restype = i
     lib.mlpmoe_forward_bf16_ws.argtypes = [vp, vp, vp, vp, ip, fp, bp, i, i, i, i, vp, vp, sz, i, vp]
@@ -269,6 +270,17 @@ def mlpmoe_forward(x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, 
 
 def mlpmoe_forward_f32(x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, out=None, stream=None):
     return _forward("mlpmoe_forward_f32", x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, out, stream)
+
+
+NOALLOC_SCRATCH_BYTES = 16 << 20
+
+
+def mlpmoe_forward_bf16_noalloc(x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, out, stream=None):
+    """The bf16 forward in the library's fixed scratch block: allocates nothing (out must be given)."""
+    if out is None:
+        raise ValueError("mlpmoe_forward_bf16_noalloc needs the output tensor")
+    return _forward("mlpmoe_forward_bf16_noalloc", x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, out,
+                    stream)
 
 
 def mlpmoe_forward_bf16_ws(x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, workspace,

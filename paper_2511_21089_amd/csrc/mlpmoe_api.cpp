@@ -29,6 +29,11 @@ struct DeviceWorkspace {
 std::mutex g_ws_mutex;
 std::map<int, DeviceWorkspace> g_ws;
 
+// Scratch of mlpmoe_forward_bf16_noalloc: device memory that exists from the moment the code
+// object is loaded, one copy per GPU.  Host code never uses this name as an address; it asks the
+// runtime for the device address once per device (noalloc_scratch) and passes that to the kernels.
+static __device__ __align__(256) unsigned char g_noalloc_scratch[MLPMOE_NOALLOC_SCRATCH_BYTES];
+
 // --- per-kernel event timing -------------------------------------------------
 struct Profiler {
     bool on = false;
@@ -239,6 +244,37 @@ int forward_owned(const void *x, const void *Wg, const void *Wu, const void *Wd,
     if (rc != MLPMOE_OK) return rc;
     return forward_impl(x, Wg, Wu, Wd, off, alpha, mask, T, d_model, d_inter, B, out, ws, ws_bytes,
                         MLPMOE_PATH_AUTO, is_bf16, stream, out_bf16);
+}
+
+// Device address of this GPU's copy of g_noalloc_scratch, asked from the runtime on the first call
+// on each device (with that device current) and kept.
+int noalloc_scratch(void **ptr)
+{
+    static std::mutex mu;
+    static void *addr[64] = {nullptr};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) {
+        (void)note_hip_error("hipGetDevice", e);
+        return MLPMOE_ERR_HIP;
+    }
+    if (dev < 0 || dev >= 64) {
+        (void)note_hip_error("device index", hipErrorInvalidDevice);
+        return MLPMOE_ERR_HIP;
+    }
+    std::lock_guard<std::mutex> lock(mu);
+    if (!addr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_noalloc_scratch));
+        if (e != hipSuccess || !p) {
+            (void)note_hip_error("hipGetSymbolAddress(noalloc scratch)", e);
+            (void)hipGetLastError();
+            return MLPMOE_ERR_HIP;
+        }
+        addr[dev] = p;
+    }
+    *ptr = addr[dev];
+    return MLPMOE_OK;
 }
 
 }  // namespace
@@ -516,6 +552,27 @@ int mlpmoe_set_workspace(void *dev_ptr, size_t bytes)
 }
 
 int mlpmoe_hidden_ld(int d_inter) { return d_inter < 0 ? 0 : h_ld(d_inter); }
+
+int mlpmoe_forward_bf16_noalloc(const void *x, const void *W_gate, const void *W_up, const void *W_down,
+                                const int32_t *branch_offsets, const float *alpha, const uint8_t *active_mask,
+                                int T, int d_model, int d_inter, int B, float *out, void *stream)
+{
+    int rc = validate_common(x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, T, d_model, d_inter, B, out);
+    if (rc != MLPMOE_OK) return rc;
+    if (T == 0) return MLPMOE_OK;
+    const size_t need = mlpmoe_workspace_bytes(T, d_model, d_inter, B, 2);
+    if (need == 0 || need > (size_t)MLPMOE_NOALLOC_SCRATCH_BYTES) {
+        snprintf(g_err_detail, sizeof(g_err_detail), "mlpmoe_forward_bf16_noalloc: needs %zu bytes of scratch, has %zu",
+                 need, (size_t)MLPMOE_NOALLOC_SCRATCH_BYTES);
+        return MLPMOE_ERR_WORKSPACE;
+    }
+    void *scratch = nullptr;
+    rc = noalloc_scratch(&scratch);
+    if (rc != MLPMOE_OK) return rc;
+    return forward_impl(x, W_gate, W_up, W_down, branch_offsets, alpha, active_mask, T, d_model, d_inter, B, out,
+                        scratch, (size_t)MLPMOE_NOALLOC_SCRATCH_BYTES, MLPMOE_PATH_AUTO, true,
+                        static_cast<hipStream_t>(stream));
+}
 
 int mlpmoe_forward_bf16_ws(const void *x, const void *W_gate, const void *W_up, const void *W_down,
                            const int32_t *branch_offsets, const float *alpha,

@@ -66,7 +66,11 @@ enum {
     MLPMOE_PATH_AUTO = 0,    /* library picks: decode for T <= 16, MFMA otherwise, generic if unaligned */
     MLPMOE_PATH_GENERIC = 1, /* LDS-tiled FMA kernels: any shape and alignment                        */
     MLPMOE_PATH_MFMA = 2,    /* bf16 MFMA prefill kernels (needs d_model%8==0 and offsets%8==0)       */
-    MLPMOE_PATH_DECODE = 3   /* weight-streaming kernels, T <= 16 (same alignment needs as MFMA)      */
+    MLPMOE_PATH_DECODE = 3,  /* weight-streaming kernels, T <= 16 (same alignment needs as MFMA)      */
+    /* MLPMOE_PATH_MFMA picks a tile shape per launch from the sizes; these force one, for both kernels   */
+    MLPMOE_PATH_MFMA_WIDE = 4,   /* 256 tokens x (128 + 128) neurons / 256 output features             */
+    MLPMOE_PATH_MFMA_NARROW = 5, /* 256 tokens x (64 + 64) neurons / 128 output features               */
+    MLPMOE_PATH_MFMA_SMALL = 6   /* 128 tokens x (64 + 64) / 128, 4 waves, two workgroups per CU       */
 };
 
 /* Human-readable name of a status code (static string, never NULL). */

@@ -270,9 +270,15 @@ decode_down_split(const uint16_t *__restrict__ Hin, int ldx, int T, const uint16
     const uint16_t *xp = Hin + (size_t)(tok ? r16 : 0) * ldx + q * 16;
     const uint16_t *zero = reinterpret_cast<const uint16_t *>(g_zero16);
 
-    // cursor over this wave's blocks: rounds of NW blocks go to the KS workgroups in turn
+    // cursor over this wave's blocks.  The K blocks of all ranges, laid end to end, are cut into KS
+    // contiguous parts, one per workgroup (a workgroup then reads long contiguous pieces of its rows);
+    // inside its part the waves take the blocks in turn.
     const int n_ranges = st.count();
-    const int first = wave + NW * (int)blockIdx.y, stride = NW * KS;
+    int nb_all = 0;
+    for (int r = 0; r < n_ranges; ++r) nb_all += (st.end(r) - st.beg(r) + KB - 1) / KB;
+    const int part = (nb_all + KS - 1) / KS;
+    const int first = wave + (int)blockIdx.y * part, stride = NW;
+    const int my_end = (int)(blockIdx.y + 1) * part < nb_all ? (int)(blockIdx.y + 1) * part : nb_all;
     int cr = 0, cb = first;
     auto settle = [&]() {                                // move past ranges the block index overshoots
         while (cr < n_ranges) {
@@ -283,20 +289,13 @@ decode_down_split(const uint16_t *__restrict__ Hin, int ldx, int T, const uint16
         }
     };
     settle();
-    int total = 0;                                       // blocks of this wave in all ranges
-    {
-        int sk = first;
-        for (int r = 0; r < n_ranges; ++r) {
-            const int nb = (st.end(r) - st.beg(r) + KB - 1) / KB;
-            const int mine = nb > sk ? (nb - sk + stride - 1) / stride : 0;
-            total += mine;
-            sk = sk + mine * stride - nb;
-        }
-    }
+    const int total = my_end > first ? (my_end - first + stride - 1) / stride : 0;   // blocks of this wave
+    int issued = 0;
 
     u32x4 wa[U][RT][2], xa[U][2];
     auto load_block = [&](int u) {                       // loads the block under the cursor, then advances
-        const bool live = cr < n_ranges;
+        const bool live = cr < n_ranges && issued < total;     // past its part a wave loads zeros
+        ++issued;
         const int k = live ? st.beg(cr) + cb * KB : 0;
         const int kend = live ? st.end(cr) : -1;
         const int kl = k + q * 16;
@@ -480,6 +479,102 @@ decode_gate_up_persist(const uint16_t *__restrict__ X, int T, const uint16_t *__
 
 // waves and ring depth of the instantiations in use: gate+up fallback, down, persistent gate+up
 constexpr int DEC_NW1 = 4, DEC_U1 = 8, DEC_NW2 = 8, DEC_U2 = 8, DEC_SNW = 8, DEC_SU = 8;
+// The persistent gate+up kernel with the x fragments held in registers instead of LDS: wave w works on
+// K blocks w, w + NW, ... of EVERY tile, so the x fragments it needs are the same for every tile and
+// are loaded once, XB blocks of 2 x 16 bytes per lane (d_model <= 64 * NW * XB).  Everything else
+// (tile order, ring of U weight blocks rolling across tiles, reduction, epilogue, clear) is
+// decode_gate_up_persist's.
+template <int NW, int U, int XB, bool kRouted = false>
+__global__ void __launch_bounds__(NW * 64)
+decode_gate_up_xreg(const uint16_t *__restrict__ X, int T, const uint16_t *__restrict__ Wg,
+                    const uint16_t *__restrict__ Wu, int d_model, uint16_t *__restrict__ Hout, int ldh,
+                    const uint8_t *__restrict__ route, float *__restrict__ clear, int clear_n, BranchTable bt)
+{
+    if (clear)
+        for (int i = blockIdx.x * (NW * 64) + threadIdx.x; i < clear_n; i += gridDim.x * (NW * 64)) clear[i] = 0.f;
+    static_assert(NW >= 4 && XB % U == 0, "the reduction uses 256 threads; ring slots are compile-time");
+    __shared__ float red[2][NW][256];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int r16 = lane & 15, q = lane >> 4;
+    const bool tok = r16 < T;
+    const uint16_t *zero = reinterpret_cast<const uint16_t *>(g_zero16);
+    const size_t lane_row_off = (size_t)(r16 & 7) * d_model + q * 16;
+    const uint16_t *wsel = r16 < 8 ? Wg : Wu;
+    const Stretches<kRouted> st{bt, kRouted ? live_branches(bt, route, T) : 0ULL};
+
+    TileCursor<kRouted> l_cur(st, blockIdx.x);
+    int l_j = 0;
+    int l_row0 = l_cur.row0(st);
+    const uint16_t *l_wrow = wsel + (size_t)(l_row0 < 0 ? 0 : l_row0) * d_model + lane_row_off;
+    u32x4 wa[U][2];
+    auto load_next = [&](int u) {
+        const int b = wave + NW * l_j;
+        const int kl = b * KB + q * 16;
+        const bool more = l_row0 >= 0;
+        wa[u][0] = ld16((more && kl < d_model) ? l_wrow + b * KB : zero);
+        wa[u][1] = ld16((more && kl + 8 < d_model) ? l_wrow + b * KB + 8 : zero);
+        if (++l_j == XB) {
+            l_j = 0;
+            l_cur.advance(st, gridDim.x);
+            l_row0 = l_cur.row0(st);
+            if (l_row0 >= 0) l_wrow = wsel + (size_t)l_row0 * d_model + lane_row_off;
+        }
+    };
+#pragma unroll
+    for (int u = 0; u < U; ++u) load_next(u);
+
+    // this wave's x fragments, once
+    u32x4 xr[XB][2];
+    {
+        const uint16_t *xp = X + (size_t)(tok ? r16 : 0) * d_model + q * 16;
+#pragma unroll
+        for (int j = 0; j < XB; ++j) {
+            const int b = wave + NW * j;
+            const int kl = b * KB + q * 16;
+            xr[j][0] = ld16((tok && kl < d_model) ? xp + b * KB : zero);
+            xr[j][1] = ld16((tok && kl + 8 < d_model) ? xp + b * KB + 8 : zero);
+        }
+    }
+
+    int it = 0;
+    TileCursor<kRouted> cur(st, blockIdx.x);
+    for (int row0 = cur.row0(st); row0 >= 0; cur.advance(st, gridDim.x), row0 = cur.row0(st), ++it) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j0 = 0; j0 < XB; j0 += U) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(wa[u][0]), as_bf16x8(xr[j0 + u][0]), acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(wa[u][1]), as_bf16x8(xr[j0 + u][1]), acc, 0, 0, 0);
+                load_next(u);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        float *rb = &red[it & 1][0][0];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) rb[wave * 256 + v * 64 + lane] = acc[v];
+        __syncthreads();
+        if (threadIdx.x < 256) {
+            const int v = threadIdx.x >> 6;
+            const int row = 4 * q + v;
+            if (row < 8 && tok) {
+                float g = 0.f, up = 0.f;
+#pragma unroll
+                for (int w = 0; w < NW; ++w) {
+                    g += rb[w * 256 + threadIdx.x];
+                    up += rb[w * 256 + threadIdx.x + 32];
+                }
+                const int n = row0 + row;
+                const int b = branch_of(bt, n);
+                float v = bt.alpha[b] * silu_mul(g, up);
+                if (kRouted) v = route[(size_t)r16 * bt.B + b] ? v : 0.f;
+                Hout[(size_t)r16 * ldh + n] = to_bf16(v);
+            }
+        }
+    }
+}
+
 constexpr size_t kStreamLdsMax = 160 * 1024;
 
 }  // namespace
@@ -494,12 +589,19 @@ static hipError_t launch_decode_impl(const FwdArgs &a, const BranchTable &bt)
     const uint16_t *X = static_cast<const uint16_t *>(a.x);
     uint16_t *H = static_cast<uint16_t *>(a.H);
     const size_t xs_bytes = (size_t)a.T * (a.d_model * 2 + 16) + 16 + 2 * DEC_SNW * 256 * sizeof(float);
+    // blocks of K per wave and tile in the persistent kernels, padded to whole ring revolutions
+    const int nb_pad = ceil_div(ceil_div(ceil_div(a.d_model, KB), DEC_SNW), DEC_SU) * DEC_SU;
+    const bool x_in_regs = nb_pad <= 16;                    // d_model <= 8192: x fragments stay in registers
+    const bool persistent = x_in_regs || xs_bytes <= kStreamLdsMax;
     // Layers with many output features take the down kernel that splits K over two workgroups and adds
     // the halves into `out` with atomics; `out` is cleared by the persistent gate+up kernel, so the
     // pair is only used together (and for a float result).
-    const bool split_down = tiles2 >= 192 && xs_bytes <= kStreamLdsMax && !a.out_bf16;
-    if (xs_bytes <= kStreamLdsMax) {
-        // per device, set up on the first call there: CU count and the kernel's LDS limit
+    const bool split_down = tiles2 >= 192 && persistent && !a.out_bf16;
+    float *clear = split_down ? a.out : nullptr;
+    const int clear_n = split_down ? a.T * a.d_model : 0;
+    const uint16_t *Wg = static_cast<const uint16_t *>(a.Wg), *Wu = static_cast<const uint16_t *>(a.Wu);
+    if (persistent) {
+        // per device, set up on the first call there: CU count and the LDS limit of the kernel that stages x
         static std::mutex mu;
         static int cus_of[64] = {0};              // one table per instantiation (attribute is per kernel)
         int dev = 0;
@@ -523,15 +625,20 @@ static hipError_t launch_decode_impl(const FwdArgs &a, const BranchTable &bt)
         }
         const int grid = tiles1 < n_cus ? (int)tiles1 : n_cus;
         ProfileScope ps(MLPMOE_KERNEL_DECODE_GATE_UP, a.stream);
-        decode_gate_up_persist<DEC_SNW, DEC_SU, kRouted><<<grid, DEC_SNW * 64, xs_bytes, a.stream>>>(
-            X, a.T, static_cast<const uint16_t *>(a.Wg), static_cast<const uint16_t *>(a.Wu), a.d_model, H,
-            a.ldh, a.route, split_down ? a.out : nullptr, split_down ? a.T * a.d_model : 0, bt);
-        if (launch_status("decode_gate_up_persist launch") != hipSuccess) return hipErrorLaunchFailure;
+        if (nb_pad <= 8)
+            decode_gate_up_xreg<DEC_SNW, DEC_SU, 8, kRouted><<<grid, DEC_SNW * 64, 0, a.stream>>>(
+                X, a.T, Wg, Wu, a.d_model, H, a.ldh, a.route, clear, clear_n, bt);
+        else if (nb_pad <= 16)
+            decode_gate_up_xreg<DEC_SNW, DEC_SU, 16, kRouted><<<grid, DEC_SNW * 64, 0, a.stream>>>(
+                X, a.T, Wg, Wu, a.d_model, H, a.ldh, a.route, clear, clear_n, bt);
+        else
+            decode_gate_up_persist<DEC_SNW, DEC_SU, kRouted><<<grid, DEC_SNW * 64, xs_bytes, a.stream>>>(
+                X, a.T, Wg, Wu, a.d_model, H, a.ldh, a.route, clear, clear_n, bt);
+        if (launch_status("decode gate+up (persistent) launch") != hipSuccess) return hipErrorLaunchFailure;
     } else {
         ProfileScope ps(MLPMOE_KERNEL_DECODE_GATE_UP, a.stream);
         decode_kernel<DEC_NW1, DEC_U1, true, kRouted><<<(unsigned)tiles1, DEC_NW1 * 64, 0, a.stream>>>(
-            X, a.d_model, a.T, static_cast<const uint16_t *>(a.Wg), static_cast<const uint16_t *>(a.Wu),
-            a.d_model, a.d_model, H, a.ldh, nullptr, 0, a.route, bt);
+            X, a.d_model, a.T, Wg, Wu, a.d_model, a.d_model, H, a.ldh, nullptr, 0, a.route, bt);
         if (launch_status("decode gate_up launch") != hipSuccess) return hipErrorLaunchFailure;
     }
     ProfileScope ps(MLPMOE_KERNEL_DECODE_DOWN, a.stream);

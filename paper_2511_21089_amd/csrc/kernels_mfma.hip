@@ -13,6 +13,8 @@
 // a WM x 2 arrangement, each wave owning (256 / WM) x (64+64) outputs as 16x16 MFMA tiles.  The
 // 16x16x32 shape is used rather than 32x32x16 because the chip is power limited on this work: with
 // random operands a pure stream of 16x16x32 MFMAs sustains 2.0 PFLOP/s, one of 32x32x16 1.7.
+#include <algorithm>
+
 #include "internal.h"
 
 namespace mlpmoe {
@@ -24,13 +26,18 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
-constexpr int BM = 256;          // tokens per tile
+constexpr int BM = 256;          // tokens per tile of the large-tile kernels (and of the routed path's tables)
+constexpr int BM_SMALL = 128;    // tokens per tile of the small-tile kernels
 constexpr int BNH_MAX = 128;     // rows of each of the two B blocks: 32 * NB, NB = 4 (128) or 2 (64)
 constexpr int BK = 64;           // K elements per tile: one tile row is 128 bytes = one cache line
-constexpr int PART_BYTES = 256 * BK * 2;             // 32768: the A rows, or the 128 + 128 B rows, of one K tile
 constexpr int N_PARTS = 5;                           // ring of parts: A0 B0 A1 B1 A2 | B2 A3 ...
-constexpr int LDS_BYTES = N_PARTS * PART_BYTES;      // 163840: the whole LDS of a CU
-constexpr int MFMA_WM = 4;                           // waves along M: 8 waves of 64 x (64+64) outputs
+// A part of the ring holds the A rows (BMT tokens), or the B rows (2 blocks of 32 NB), of one K tile.
+// 256-token tiles: 32 KiB parts, the ring is the whole LDS of a CU (one workgroup of 8 waves per CU).
+// 128-token tiles with NB = 2: 16 KiB parts, 80 KiB per workgroup of 4 waves, two workgroups per CU.
+__host__ __device__ constexpr int part_bytes(int bmt, int nb) { return (bmt > 64 * nb ? bmt : 64 * nb) * BK * 2; }
+__host__ __device__ constexpr int lds_bytes(int bmt, int nb) { return N_PARTS * part_bytes(bmt, nb); }
+constexpr int MFMA_WM = 4;                           // waves along M of the 256-token tiles: 8 waves of 64 x (64+64) outputs
+constexpr int SMALL_WM = 2;                          // ... of the 128-token tiles: 4 waves of 64 x (32+32)
 
 // 16 zero bytes: K chunks that fall past the end of a range are fetched from here.
 __device__ const uint32_t g_zero_chunk[4] = {0, 0, 0, 0};
@@ -152,21 +159,24 @@ __device__ __forceinline__ KCursor k_seek(const KR &kr, int tile)
 // NB = 16-row MFMA pieces per B block per wave: 4 (B blocks of 128 rows, a 256 x 256 tile) or 2 (B
 // blocks of 64 rows, a 256 x 128 tile, for shapes that would otherwise leave most CUs without a
 // tile in the last round).  A B part of 64 + 64 rows fills half of its ring slot.
-template <int WM, int NB, bool kRowsAreB, typename KR>
+template <int BMT, int WM, int NB, bool kRowsAreB, typename KR>
 __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, int lda, int a_valid,
                                          const uint16_t *__restrict__ B0_tile,
                                          const uint16_t *__restrict__ B1_tile, int ldb, int b0_valid,
                                          int b1_valid, const KR &kr, int kt_begin, int kt_end, char *lds,
-                                         f32x4 (&acc0)[16 / WM][NB], f32x4 (&acc1)[16 / WM][NB])
+                                         f32x4 (&acc0)[BMT / 16 / WM][NB], f32x4 (&acc1)[BMT / 16 / WM][NB])
 {
-    constexpr int MI = 16 / WM;                   // 16-row MFMA tiles per wave along M: 8 or 4
+    constexpr int MI = BMT / 16 / WM;             // 16-row MFMA tiles per wave along M
     constexpr int NWAVES = WM * 2;
     constexpr int BNH = 32 * NB;                  // rows of each B block
-    constexpr int PL = 32 / NWAVES;               // 1 KiB wave-loads per wave per A part: 8 or 4
+    constexpr int PL = BMT / 8 / NWAVES;          // 1 KiB wave-loads per wave per A part
     constexpr int PLB = 8 * NB / NWAVES;          // ... per B part
     constexpr int N_SLOTS = MI * NB / 2;          // slots of 4 MFMAs per K step
     constexpr int N_PIECES = 2 * NB + MI;         // fragment pieces per K step
-    static_assert(N_SLOTS % PL == 0 && N_SLOTS % PLB == 0 && PLB % 2 == 0, "loads spread evenly over the slots");
+    constexpr int PART_BYTES = part_bytes(BMT, NB);
+    static_assert(N_SLOTS % PL == 0 && N_SLOTS % PLB == 0 && PL % 2 == 0 && PLB % 2 == 0,
+                  "loads spread evenly over the slots, slab parity is load parity");
+    static_assert(2 * N_SLOTS >= N_PIECES, "two fragment reads per slot cover a K step");
     const int nk = kt_end - kt_begin;
     if (nk <= 0) return;
     const int tid = threadIdx.x;
@@ -411,14 +421,15 @@ struct RouteTiles {
 // over the full grid (one contiguous stretch of the list per XCD), the ids left over exit.  The
 // down projection skips the same (token tile, branch) pairs, and H is multiplied by the token's
 // route bit, so that it is exactly 0 where a token does not take a branch.
-template <int WM, int NB, bool kRouted>
+template <int BMT, int WM, int NB, bool kRouted>
 __global__ void __launch_bounds__(WM * 128)
 gate_up_mfma(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
              const uint16_t *__restrict__ Wu, uint16_t *__restrict__ H, int T, int d_model, int d_inter,
              int ldh, int tiles_m, int tiles_n, const uint8_t *__restrict__ route, RouteTiles rt,
              BranchTable bt)
 {
-    __shared__ __attribute__((aligned(1024))) char lds[LDS_BYTES];
+    static_assert(!kRouted || BMT == BM, "the routed path's tables are per 256 tokens");
+    __shared__ __attribute__((aligned(1024))) char lds[lds_bytes(BMT, NB)];
     constexpr int BNH = 32 * NB;                  // neurons per tile
     int tm, tn;
     if (kRouted) {
@@ -454,9 +465,9 @@ gate_up_mfma(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
         tn -= n;
     }
     if (n_end == 0) return;
-    const int t0 = tm * BM;
+    const int t0 = tm * BMT;
 
-    constexpr int MI = 16 / WM;
+    constexpr int MI = BMT / 16 / WM;
     f32x4 accg[MI][NB], accu[MI][NB];
 #pragma unroll
     for (int i = 0; i < MI; ++i)
@@ -467,7 +478,7 @@ gate_up_mfma(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
         }
 
     const int nk = (d_model + BK - 1) / BK;
-    mainloop<WM, NB, true>(X + (size_t)t0 * d_model, d_model, T - t0, Wg + (size_t)n0 * d_model,
+    mainloop<BMT, WM, NB, true>(X + (size_t)t0 * d_model, d_model, T - t0, Wg + (size_t)n0 * d_model,
                        Wu + (size_t)n0 * d_model, d_model, n_end - n0, n_end - n0, KSingle{d_model}, 0, nk,
                        lds, accg, accu);
 
@@ -514,19 +525,20 @@ gate_up_mfma(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
 // dst_bf16 (only with splits == 1): dst holds bf16 values, each sum is rounded once (RNE).
 // kRouted: the K loop of token tile tm walks only the branches some token of the tile is routed
 // to (tile_need); H is 0 for the tokens of the tile that do not take a branch.
-template <int WM, int NB, bool kRouted>
+template <int BMT, int WM, int NB, bool kRouted>
 __global__ void __launch_bounds__(WM * 128)
 down_mfma(const uint16_t *__restrict__ H, const uint16_t *__restrict__ Wd, float *__restrict__ dst, int T,
           int d_model, int d_inter, int ldh, int tiles_m, int tiles_n, int splits, int kt_total, int dst_bf16,
           const uint8_t *__restrict__ tile_need, BranchTable bt)
 {
-    __shared__ __attribute__((aligned(1024))) char lds[LDS_BYTES];
+    static_assert(!kRouted || BMT == BM, "the routed path's tables are per 256 tokens");
+    __shared__ __attribute__((aligned(1024))) char lds[lds_bytes(BMT, NB)];
     const int per_split = XCDS * ids_per_xcd((long long)tiles_m * tiles_n);
     const int z = blockIdx.x / per_split;
     int tm, tn;
     if (!tile_of(blockIdx.x % per_split, tiles_m, tiles_n, tm, tn)) return;
     constexpr int BNH = 32 * NB;                  // output features per B block; a tile has two
-    const int t0 = tm * BM, n0 = tn * (2 * BNH);
+    const int t0 = tm * BMT, n0 = tn * (2 * BNH);
     KRunsLanes dyn{0, 0, 0};
     if (kRouted) {
         dyn = routed_runs(bt, tile_need + (size_t)tm * bt.B);
@@ -536,7 +548,7 @@ down_mfma(const uint16_t *__restrict__ H, const uint16_t *__restrict__ Wd, float
     const int kt_begin = (int)((long long)kt_total * z / splits);
     const int kt_end = (int)((long long)kt_total * (z + 1) / splits);
 
-    constexpr int MI = 16 / WM;
+    constexpr int MI = BMT / 16 / WM;
     f32x4 acc0[MI][NB], acc1[MI][NB];
 #pragma unroll
     for (int i = 0; i < MI; ++i)
@@ -549,13 +561,13 @@ down_mfma(const uint16_t *__restrict__ H, const uint16_t *__restrict__ Wd, float
     // the second block of output features may start past d_model: point it at the last row
     const int n1 = n0 + BNH < d_model ? n0 + BNH : d_model - 1;
     if (kRouted)
-        mainloop<WM, NB, true>(H + (size_t)t0 * ldh, ldh, T - t0, Wd + (size_t)n0 * d_inter,
-                               Wd + (size_t)n1 * d_inter, d_inter, d_model - n0, d_model - n1, dyn, kt_begin, kt_end,
-                               lds, acc0, acc1);
+        mainloop<BMT, WM, NB, true>(H + (size_t)t0 * ldh, ldh, T - t0, Wd + (size_t)n0 * d_inter,
+                                    Wd + (size_t)n1 * d_inter, d_inter, d_model - n0, d_model - n1, dyn, kt_begin,
+                                    kt_end, lds, acc0, acc1);
     else
-        mainloop<WM, NB, true>(H + (size_t)t0 * ldh, ldh, T - t0, Wd + (size_t)n0 * d_inter,
-                               Wd + (size_t)n1 * d_inter, d_inter, d_model - n0, d_model - n1, KRuns{bt}, kt_begin,
-                               kt_end, lds, acc0, acc1);
+        mainloop<BMT, WM, NB, true>(H + (size_t)t0 * ldh, ldh, T - t0, Wd + (size_t)n0 * d_inter,
+                                    Wd + (size_t)n1 * d_inter, d_inter, d_model - n0, d_model - n1, KRuns{bt},
+                                    kt_begin, kt_end, lds, acc0, acc1);
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -739,30 +751,93 @@ int k_tiles(const BranchTable &bt)
     return n;
 }
 
-// Split-K factor of the down projection for output tiles of 256 x tile_n.
-int down_splits(int T, int d_model, int k_elems, int tile_n)
+// Tile shapes.  WIDE: 256 tokens x (128 + 128) rows of B, the shape with the most reuse per byte moved
+// into the LDS.  NARROW: 256 x (64 + 64).  SMALL: 128 x (64 + 64) with 4 waves and 80 KiB of LDS, two
+// workgroups per CU: four times the tiles of WIDE, the fixed cost of one workgroup (first loads,
+// epilogue, hand-over) hidden under the main loop of the other, at 1.6 times WIDE's traffic into the
+// LDS per flop.  For layers and batches that give WIDE too few or too short tiles.
+enum TileShape { TILE_WIDE = 0, TILE_NARROW = 1, TILE_SMALL = 2 };
+struct TileDims {
+    int bm, bn;       // tokens, B rows per block (a tile has two blocks)
+    int per_cu;       // workgroups resident per CU
+};
+constexpr TileDims kTileDims[3] = {{BM, 128, 1}, {BM, 64, 1}, {BM_SMALL, 64, 2}};
+constexpr int kCUs = 256;
+
+long long gate_up_tiles(const BranchTable &bt, int T, TileShape sh)
 {
-    const long long tiles = (long long)ceil_div(T, BM) * ceil_div(d_model, tile_n);
+    long long n = 0;
+    for (int r = 0; r < bt.n_runs; ++r) n += ceil_div(bt.run_end[r] - bt.run_start[r], kTileDims[sh].bn);
+    return n * ceil_div(T, kTileDims[sh].bm);
+}
+
+// Estimated duration of a launch of `tiles` tiles with nk K tiles each, in units of one K tile of a
+// WIDE tile.  Per K tile a NARROW tile costs 0.55 and a SMALL one 0.4 (two of them share a CU, each
+// at 0.2 of a WIDE tile's flops but bound by the traffic into the LDS); the fixed cost of a
+// workgroup is about 5 / 3.5 units, and about 1 for SMALL, whose neighbour on the CU computes meanwhile.
+double launch_cost(long long tiles, int nk, TileShape sh)
+{
+    static const double per_k[3] = {1.0, 0.55, 0.4}, fixed[3] = {5.0, 3.5, 1.0};
+    const long long per_cu = (tiles + kCUs - 1) / kCUs;       // tiles the busiest CU runs, one after the other
+    if (sh == TILE_SMALL) {
+        // two at a time: an odd one at the end runs alone, at its own speed (about 0.3 per K tile)
+        return (double)(per_cu / 2) * 2 * (nk * per_k[sh] + fixed[sh]) + (double)(per_cu % 2) * (nk * 0.3 + 3.0);
+    }
+    return (double)per_cu * (nk * per_k[sh] + fixed[sh]);
+}
+
+TileShape pick_gate_up_tile(const BranchTable &bt, int T, int d_model)
+{
+    const int nk = ceil_div(d_model, BK);
+    TileShape best = TILE_WIDE;
+    double best_cost = launch_cost(gate_up_tiles(bt, T, TILE_WIDE), nk, TILE_WIDE);
+    for (TileShape sh : {TILE_NARROW, TILE_SMALL}) {
+        const double c = launch_cost(gate_up_tiles(bt, T, sh), nk, sh);
+        if (c < best_cost * 0.97) {
+            best = sh;
+            best_cost = c;
+        }
+    }
+    return best;
+}
+
+// Split-K factor of the down projection: fills the chip when the output has few tiles.
+int down_splits(int T, int d_model, int k_elems, TileShape sh)
+{
+    const TileDims &d = kTileDims[sh];
+    const long long tiles = (long long)ceil_div(T, d.bm) * ceil_div(d_model, 2 * d.bn);
     const int kt = ceil_div(k_elems > 0 ? k_elems : 1, BK);
-    long long s = 256 / tiles;
+    long long s = (long long)kCUs * d.per_cu / tiles;
     if (s > kt / 4) s = kt / 4;
     if (s > 32) s = 32;
     return s < 1 ? 1 : (int)s;
 }
 
-// Which tile width to use for `tiles` wide tiles on a chip that runs 256 at a time: narrow tiles
-// (half the neurons / output features) take about 0.55 of a wide tile's time, so they pay off when
-// the wide tiles' last round would be mostly empty.
-bool narrow_tiles_pay(long long wide_tiles)
+TileShape pick_down_tile(int T, int d_model, int k_elems)
 {
-    const long long rounds_wide = (wide_tiles + 255) / 256;
-    const double rounds_narrow = (double)((2 * wide_tiles + 255) / 256) * 0.55;
-    return rounds_narrow < (double)rounds_wide * 0.97;
+    // the partial sums of a split K are written and read again: narrow tiles halve them
+    if (down_splits(T, d_model, k_elems, TILE_WIDE) == 1) return TILE_WIDE;
+    const int kt = ceil_div(k_elems > 0 ? k_elems : 1, BK);
+    TileShape best = TILE_NARROW;
+    double best_cost = 1e30;
+    for (TileShape sh : {TILE_NARROW, TILE_SMALL}) {
+        const TileDims &d = kTileDims[sh];
+        const int sp = down_splits(T, d_model, k_elems, sh);
+        const long long tiles = (long long)ceil_div(T, d.bm) * ceil_div(d_model, 2 * d.bn) * sp;
+        // partial sums: sp * T * d_model floats written and read back, at about 3 TB/s; a unit is about 1.5 us
+        const double partial_units = sp > 1 ? 2.0 * sp * (double)T * d_model * 4.0 / 3e12 / 1.5e-6 : 0.0;
+        const double c = launch_cost(tiles, ceil_div(kt, sp), sh) + partial_units;
+        if (c < best_cost) {
+            best = sh;
+            best_cost = c;
+        }
+    }
+    return best;
 }
 
 }  // namespace
 
-int mfma_down_splits(int T, int d_model, int k_elems) { return down_splits(T, d_model, k_elems, 2 * BNH_MAX); }
+int mfma_down_splits(int T, int d_model, int k_elems) { return down_splits(T, d_model, k_elems, TILE_WIDE); }
 
 // Layout of the routed kernels' scratch block (256-byte aligned): tile_need, counts, list.
 // The list holds, per group of GROUP_M token tiles, up to GROUP_M * (N tiles) entries; the N tiles
@@ -784,14 +859,16 @@ size_t route_scratch_bytes(int T, int d_inter)
 
 size_t mfma_partial_bytes(int T, int d_model, int d_inter)
 {
-    // sized for the wide tiles: narrow tiles double the tile count and so never split more
-    const int s = mfma_down_splits(T, d_model, d_inter);
+    // the largest any tile shape asks for
+    int s = 1;
+    for (TileShape sh : {TILE_WIDE, TILE_NARROW, TILE_SMALL}) s = std::max(s, down_splits(T, d_model, d_inter, sh));
     return s > 1 ? align_up((size_t)s * T * d_model * sizeof(float), 256) : 0;
 }
 
-template <int NB, bool kRouted = false>
-static hipError_t launch_gate_up(const FwdArgs &a, const BranchTable &bt, int tiles_m)
+template <int BMT, int WM, int NB, bool kRouted = false>
+static hipError_t launch_gate_up(const FwdArgs &a, const BranchTable &bt)
 {
+    const int tiles_m = ceil_div(a.T, BMT);
     long long tiles_n = 0;
     for (int r = 0; r < bt.n_runs; ++r) tiles_n += ceil_div(bt.run_end[r] - bt.run_start[r], 32 * NB);
     const long long grid = (long long)XCDS * ids_per_xcd(tiles_m * tiles_n);
@@ -815,46 +892,42 @@ static hipError_t launch_gate_up(const FwdArgs &a, const BranchTable &bt, int ti
         rt = RouteTiles{need, counts, list, stride};
     }
     ProfileScope ps(MLPMOE_KERNEL_GATE_UP_MFMA, a.stream);
-    gate_up_mfma<MFMA_WM, NB, kRouted><<<(unsigned)grid, MFMA_WM * 128, 0, a.stream>>>(
+    gate_up_mfma<BMT, WM, NB, kRouted><<<(unsigned)grid, WM * 128, 0, a.stream>>>(
         static_cast<const uint16_t *>(a.x), static_cast<const uint16_t *>(a.Wg),
         static_cast<const uint16_t *>(a.Wu), static_cast<uint16_t *>(a.H), a.T, a.d_model, a.d_inter,
         a.ldh, tiles_m, (int)tiles_n, a.route, rt, bt);
     return launch_status("gate_up_mfma launch");
 }
 
-template <int NB, bool kRouted = false>
-static hipError_t launch_down(const FwdArgs &a, const BranchTable &bt, int tiles_m, int kt_total, int *splits_out)
+template <int BMT, int WM, int NB, bool kRouted = false>
+static hipError_t launch_down(const FwdArgs &a, const BranchTable &bt, int splits)
 {
-    const int tile_n = 64 * NB;
-    const int tiles_n = ceil_div(a.d_model, tile_n);
-    // splits from the active width: never more than the workspace was sized for (d_inter >= d_eff)
-    int splits = down_splits(a.T, a.d_model, bt.d_eff, tile_n);
-    if (splits > kt_total) splits = kt_total;
-    if (splits > 1 && (size_t)splits * a.T * a.d_model * sizeof(float) > a.partial_bytes) splits = 1;
+    const int tiles_m = ceil_div(a.T, BMT);
+    const int tiles_n = ceil_div(a.d_model, 64 * NB);
+    const int kt_total = k_tiles(bt);
     const long long grid = (long long)XCDS * ids_per_xcd((long long)tiles_m * tiles_n) * splits;
     if (grid > 0x7fffffffLL) return note_hip_error("down_mfma grid", hipErrorInvalidValue);
-    *splits_out = splits;
     ProfileScope ps(MLPMOE_KERNEL_DOWN_MFMA, a.stream);
-    down_mfma<MFMA_WM, NB, kRouted><<<(unsigned)grid, MFMA_WM * 128, 0, a.stream>>>(
+    down_mfma<BMT, WM, NB, kRouted><<<(unsigned)grid, WM * 128, 0, a.stream>>>(
         static_cast<const uint16_t *>(a.H), static_cast<const uint16_t *>(a.Wd), splits > 1 ? a.partial : a.out,
         a.T, a.d_model, a.d_inter, a.ldh, tiles_m, tiles_n, splits, kt_total, (a.out_bf16 && splits == 1) ? 1 : 0,
         a.route_scratch, bt);
     return launch_status("down_mfma launch");
 }
 
-// Per-token routing on the MFMA kernels (wide tiles: how many tiles are live is known only on the
-// device).  a.route_scratch is route_scratch_bytes(T, d_inter) bytes, 256-byte aligned.
-hipError_t launch_mfma_routed_bf16(const FwdArgs &a, const BranchTable &bt)
+// The down projection with the tile shape and K split chosen for the call, then the sum of the
+// partial results if K was split.  The split is taken from the active width (never more than the
+// workspace was sized for, d_inter >= d_eff) and never exceeds the K tiles there are.
+template <bool kRouted>
+static hipError_t down_and_reduce(const FwdArgs &a, const BranchTable &bt, TileShape sh)
 {
-    const int tiles_m = ceil_div(a.T, BM);
-    hipError_t e = launch_gate_up<4, true>(a, bt, tiles_m);
-    if (e != hipSuccess) return hipErrorLaunchFailure;
-    // the down projection takes the tile width and the K split the unrouted launch takes, so that a
-    // route of all ones adds up every output in the same order and gives the same bits
-    const bool narrow2 = down_splits(a.T, a.d_model, bt.d_eff, 2 * BNH_MAX) > 1;
-    int splits = 1;
-    e = narrow2 ? launch_down<2, true>(a, bt, tiles_m, k_tiles(bt), &splits)
-                : launch_down<4, true>(a, bt, tiles_m, k_tiles(bt), &splits);
+    int splits = down_splits(a.T, a.d_model, bt.d_eff, sh);
+    splits = std::min(splits, std::max(1, k_tiles(bt)));
+    if (splits > 1 && (size_t)splits * a.T * a.d_model * sizeof(float) > a.partial_bytes) splits = 1;
+    hipError_t e;
+    if (sh == TILE_WIDE) e = launch_down<BM, MFMA_WM, 4, kRouted>(a, bt, splits);
+    else if (sh == TILE_NARROW) e = launch_down<BM, MFMA_WM, 2, kRouted>(a, bt, splits);
+    else e = kRouted ? hipErrorInvalidValue : launch_down<BM_SMALL, SMALL_WM, 2, false>(a, bt, splits);
     if (e != hipSuccess) return hipErrorLaunchFailure;
     if (splits > 1) {
         ProfileScope ps(MLPMOE_KERNEL_SPLITK_REDUCE, a.stream);
@@ -866,30 +939,27 @@ hipError_t launch_mfma_routed_bf16(const FwdArgs &a, const BranchTable &bt)
     return launch_status("reduce_partials launch");
 }
 
+// Per-token routing on the MFMA kernels (wide tiles: how many tiles are live is known only on the
+// device).  a.route_scratch is route_scratch_bytes(T, d_inter) bytes, 256-byte aligned.
+hipError_t launch_mfma_routed_bf16(const FwdArgs &a, const BranchTable &bt)
+{
+    hipError_t e = launch_gate_up<BM, MFMA_WM, 4, true>(a, bt);
+    if (e != hipSuccess) return hipErrorLaunchFailure;
+    // 256-token tiles (the routing tables are per 256 tokens); narrow when K is split, as the
+    // unrouted launch did before it had other shapes to choose from
+    const bool narrow = down_splits(a.T, a.d_model, bt.d_eff, TILE_WIDE) > 1;
+    return down_and_reduce<true>(a, bt, narrow ? TILE_NARROW : TILE_WIDE);
+}
+
 hipError_t launch_mfma_bf16(const FwdArgs &a, const BranchTable &bt)
 {
-    const int tiles_m = ceil_div(a.T, BM);
-    long long wide1 = 0;
-    for (int r = 0; r < bt.n_runs; ++r) wide1 += ceil_div(bt.run_end[r] - bt.run_start[r], BNH_MAX);
-    wide1 *= tiles_m;
-    hipError_t e = narrow_tiles_pay(wide1) ? launch_gate_up<2>(a, bt, tiles_m) : launch_gate_up<4>(a, bt, tiles_m);
+    const TileShape gu = a.tile_shape >= 0 ? (TileShape)a.tile_shape : pick_gate_up_tile(bt, a.T, a.d_model);
+    hipError_t e = gu == TILE_WIDE     ? launch_gate_up<BM, MFMA_WM, 4>(a, bt)
+                   : gu == TILE_NARROW ? launch_gate_up<BM, MFMA_WM, 2>(a, bt)
+                                       : launch_gate_up<BM_SMALL, SMALL_WM, 2>(a, bt);
     if (e != hipSuccess) return hipErrorLaunchFailure;
-
-    const int kt_total = k_tiles(bt);
-    // the down projection fills the chip by splitting K; narrow tiles halve the partial sums that
-    // have to be written and added up again, so they pay whenever K is split
-    const bool narrow2 = down_splits(a.T, a.d_model, bt.d_eff, 2 * BNH_MAX) > 1;
-    int splits = 1;
-    e = narrow2 ? launch_down<2>(a, bt, tiles_m, kt_total, &splits) : launch_down<4>(a, bt, tiles_m, kt_total, &splits);
-    if (e != hipSuccess) return hipErrorLaunchFailure;
-    if (splits > 1) {
-        ProfileScope ps(MLPMOE_KERNEL_SPLITK_REDUCE, a.stream);
-        const size_t n = (size_t)a.T * a.d_model;
-        size_t blocks = (n + 255) / 256;
-        if (blocks > 8192) blocks = 8192;
-        reduce_partials<<<(unsigned)blocks, 256, 0, a.stream>>>(a.partial, a.out, n, splits, a.out_bf16 ? 1 : 0);
-    }
-    return launch_status("reduce_partials launch");
+    return down_and_reduce<false>(a, bt, a.tile_shape >= 0 ? (TileShape)a.tile_shape
+                                                              : pick_down_tile(a.T, a.d_model, bt.d_eff));
 }
 
 }  // namespace mlpmoe

@@ -104,6 +104,26 @@ def test_bf16_mfma_path(mm, T, dm, off, mask):
     assert np.array_equal(got, again)                      # bitwise reproducible
 
 
+MFMA_TILE_CASES = MFMA_CASES + [
+    (600, 200, [0, 64, 192, 200, 776, 1416], [1, 1, 1, 0, 1]),   # five 128-token tiles (tail of 88), runs of 200 and 640
+    (129, 1032, [0, 1096], [1]),                                  # 17 K tiles (tail of 8), one token past a tile
+    (1000, 384, [0, 520, 1040], [1, 1]),                          # enough output tiles for several K splits
+]
+
+
+@pytest.mark.parametrize("T,dm,off,mask", MFMA_TILE_CASES)
+def test_bf16_mfma_every_tile_shape(mm, T, dm, off, mask):
+    """Each tile shape of the MFMA kernels forced for both launches (256 x (128+128), 256 x (64+64), 128 x (64+64)):
+    H and the result element by element, bitwise reproducible."""
+    args = small_bf16_case(900 + T, T, dm, off, mask)
+    for p in (mm.PATH_MFMA_WIDE, mm.PATH_MFMA_NARROW, mm.PATH_MFMA_SMALL):
+        got, H = run_gpu_with_hidden(*args, path=p)
+        check_bf16_flip_aware(got, H, *args, label="T=%d d_model=%d tile shape %d:" % (T, dm, p - mm.PATH_MFMA_WIDE))
+        if sum(w for w, m in zip(np.diff(off), mask) if m) >= 1000:
+            check_bf16(got, args)
+        assert np.array_equal(got, run_gpu(*args, path=p))
+
+
 DECODE_CASES = [
     (1, 136, [0, 520, 520, 904, 1672], [1, 1, 0, 1]),
     (5, 264, [0, 8, 264, 272, 1400], [1, 0, 1, 1]),
@@ -111,6 +131,26 @@ DECODE_CASES = [
     (8, 64, [0, 1048], [1]),
     (16, 1096, [0, 1000, 2072], [1, 1]),                   # K tails in both kernels
 ]
+
+
+WIDE_MODEL_DECODE_CASES = [
+    # d_model beyond 4096: the gate+up kernel variants (x fragments of 16 blocks in registers; x staged in LDS;
+    # one workgroup per tile) and the down kernel that splits K over two workgroups
+    (16, 4104, [0, 64, 136], [1, 1]),                      # 65 K blocks: 9 per wave, padded to 16
+    (5, 8192, [0, 72], [1]),
+    (3, 8200, [0, 64, 128], [1, 1]),                       # 129 K blocks: x staged in LDS
+    (16, 8200, [0, 64, 128], [0, 1]),                      # ... too large for the LDS at 16 tokens
+]
+
+
+@pytest.mark.parametrize("T,dm,off,mask", WIDE_MODEL_DECODE_CASES)
+def test_bf16_decode_wide_models(mm, T, dm, off, mask):
+    args = small_bf16_case(300 + T + dm, T, dm, off, mask, w_scale=0.02)
+    got, H = run_gpu_with_hidden(*args, path=mm.PATH_DECODE)
+    check_bf16_flip_aware(got, H, *args, label="decode T=%d d_model=%d:" % (T, dm))
+    assert np.array_equal(got, run_gpu(*args, path=mm.PATH_DECODE))
+    g2, H2 = run_gpu_with_hidden(*args, path=mm.PATH_GENERIC)
+    check_bf16_flip_aware(g2, H2, *args, label="generic T=%d d_model=%d:" % (T, dm))
 
 
 @pytest.mark.parametrize("T,dm,off,mask", DECODE_CASES)
@@ -300,7 +340,8 @@ def test_bf16_thin_layers_every_path(mm, T, dm, off, mask):
     """Layers with 8 .. 512 active neurons in contract AND exact mode on the generic, MFMA and decode kernels:
     the stored intermediate is compared element by element, and the outputs with the flips accounted for."""
     args = small_bf16_case(500 + T + dm, T, dm, off, mask)
-    paths = [mm.PATH_GENERIC, mm.PATH_MFMA] + ([mm.PATH_DECODE] if T <= 16 else [])
+    paths = [mm.PATH_GENERIC, mm.PATH_MFMA, mm.PATH_MFMA_WIDE, mm.PATH_MFMA_NARROW, mm.PATH_MFMA_SMALL] + (
+        [mm.PATH_DECODE] if T <= 16 else [])
     for p in paths:
         got, H = run_gpu_with_hidden(*args, path=p)
         check_bf16_flip_aware(got, H, *args, label="thin T=%d d_model=%d path=%d:" % (T, dm, p))

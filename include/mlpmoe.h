@@ -70,7 +70,9 @@ enum {
     /* MLPMOE_PATH_MFMA picks a tile shape per launch from the sizes; these force one, for both kernels   */
     MLPMOE_PATH_MFMA_WIDE = 4,   /* 256 tokens x (128 + 128) neurons / 256 output features             */
     MLPMOE_PATH_MFMA_NARROW = 5, /* 256 tokens x (64 + 64) neurons / 128 output features               */
-    MLPMOE_PATH_MFMA_SMALL = 6   /* 128 tokens x (64 + 64) / 128, 4 waves, two workgroups per CU       */
+    MLPMOE_PATH_MFMA_SMALL = 6,  /* 128 tokens x (64 + 64) / 128, 4 waves, two workgroups per CU       */
+    MLPMOE_PATH_MFMA_MIXED = 7   /* gate+up: WIDE for the full rounds of 256 workgroups, NARROW for a
+                                    remainder of at most half a round (WIDE if there is none); down: chosen */
 };
 
 /* Human-readable name of a status code (static string, never NULL). */

@@ -39,6 +39,8 @@ __host__ __device__ constexpr int lds_bytes(int bmt, int nb) { return N_PARTS * 
 constexpr int MFMA_WM = 4;                           // waves along M of the 256-token tiles: 8 waves of 64 x (64+64) outputs
 constexpr int SMALL_WM = 2;                          // ... of the 128-token tiles: 4 waves of 64 x (32+32)
 
+enum { DST_F32 = 0, DST_BF16 = 1 };     // how down_mfma writes its result
+
 // 16 zero bytes: K chunks that fall past the end of a range are fetched from here.
 __device__ const uint32_t g_zero_chunk[4] = {0, 0, 0, 0};
 
@@ -388,6 +390,16 @@ __device__ __forceinline__ uint16_t to_bf16(float v)
 constexpr int XCDS = 8;
 constexpr int GROUP_M = 8;
 __host__ __device__ inline int ids_per_xcd(long long tiles) { return (int)((tiles + XCDS - 1) / XCDS); }
+// position in the grouped tile order -> tile
+__device__ __forceinline__ void tile_from_logical(int logical, int tiles_m, int tiles_n, int &tm, int &tn)
+{
+    const int group_sz = GROUP_M * tiles_n;
+    const int g = logical / group_sz, rem = logical % group_sz;
+    const int m0 = g * GROUP_M;
+    const int gsz = tiles_m - m0 < GROUP_M ? tiles_m - m0 : GROUP_M;
+    tm = m0 + rem % gsz;
+    tn = rem / gsz;
+}
 __device__ __forceinline__ bool tile_of(int id, int tiles_m, int tiles_n, int &tm, int &tn)
 {
     const int total = tiles_m * tiles_n;
@@ -415,56 +427,31 @@ struct RouteTiles {
     int stride;
 };
 
-// grid.x = 8 * ids_per_xcd(tilesM * sum over runs of N tiles).
-// kRouted: per-token routing.  route[t * B + b] != 0 says token t takes branch b.  Only the live
-// tiles are computed: workgroup ids are dealt over the compacted tile list as tile_of() deals them
-// over the full grid (one contiguous stretch of the list per XCD), the ids left over exit.  The
-// down projection skips the same (token tile, branch) pairs, and H is multiplied by the token's
-// route bit, so that it is exactly 0 where a token does not take a branch.
-template <int BMT, int WM, int NB, bool kRouted>
-__global__ void __launch_bounds__(WM * 128)
-gate_up_mfma(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
-             const uint16_t *__restrict__ Wu, uint16_t *__restrict__ H, int T, int d_model, int d_inter,
-             int ldh, int tiles_m, int tiles_n, const uint8_t *__restrict__ route, RouteTiles rt,
-             BranchTable bt)
+// N tile tn (counted over the runs of active branches, tiles of bnh neurons) -> its first neuron and
+// the end of its run; false past the last tile.
+__device__ __forceinline__ bool neuron_tile(const BranchTable &bt, int tn, int bnh, int &n0, int &n_end)
 {
-    static_assert(!kRouted || BMT == BM, "the routed path's tables are per 256 tokens");
-    __shared__ __attribute__((aligned(1024))) char lds[lds_bytes(BMT, NB)];
-    constexpr int BNH = 32 * NB;                  // neurons per tile
-    int tm, tn;
-    if (kRouted) {
-        const int groups = (tiles_m + GROUP_M - 1) / GROUP_M;
-        int total = 0;
-        for (int g = 0; g < groups; ++g) total += (int)rt.counts[g];
-        const int per_xcd = ids_per_xcd(total);
-        const int k = blockIdx.x / XCDS;
-        const int logical = (blockIdx.x % XCDS) * per_xcd + k;
-        if (k >= per_xcd || logical >= total) return;
-        int g = 0, before = 0;
-        for (; g < groups - 1; ++g) {
-            const int c = (int)rt.counts[g];
-            if (logical < before + c) break;
-            before += c;
-        }
-        const int e = (int)rt.list[(size_t)g * rt.stride + (logical - before)];
-        const int m0 = g * GROUP_M;
-        const int gsz = tiles_m - m0 < GROUP_M ? tiles_m - m0 : GROUP_M;
-        tm = m0 + e % gsz;
-        tn = e / gsz;
-    } else if (!tile_of(blockIdx.x, tiles_m, tiles_n, tm, tn)) {
-        return;
-    }
-    int n0 = 0, n_end = 0;
     for (int r = 0; r < bt.n_runs; ++r) {
-        const int n = (bt.run_end[r] - bt.run_start[r] + BNH - 1) / BNH;
+        const int n = (bt.run_end[r] - bt.run_start[r] + bnh - 1) / bnh;
         if (tn < n) {
-            n0 = bt.run_start[r] + tn * BNH;
+            n0 = bt.run_start[r] + tn * bnh;
             n_end = bt.run_end[r];
-            break;
+            return true;
         }
         tn -= n;
     }
-    if (n_end == 0) return;
+    return false;
+}
+
+// One tile of the gate+up projection: tokens tm * BMT .., neurons n0 .. min(n0 + 32 NB, n_end) of a run that
+// ends at n_end.  lds: lds_bytes(BMT, NB) bytes.
+template <int BMT, int WM, int NB, bool kRouted>
+__device__ __forceinline__ void gate_up_tile(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
+                                             const uint16_t *__restrict__ Wu, uint16_t *__restrict__ H, int T,
+                                             int d_model, int ldh, const uint8_t *__restrict__ route,
+                                             const BranchTable &bt, char *lds, int tm, int n0, int n_end)
+{
+    constexpr int BNH = 32 * NB;
     const int t0 = tm * BMT;
 
     constexpr int MI = BMT / 16 / WM;
@@ -521,14 +508,97 @@ gate_up_mfma(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
     }
 }
 
+// grid.x = 8 * ids_per_xcd(tilesM * sum over runs of N tiles).
+// kRouted: per-token routing.  route[t * B + b] != 0 says token t takes branch b.  Only the live
+// tiles are computed: workgroup ids are dealt over the compacted tile list as tile_of() deals them
+// over the full grid (one contiguous stretch of the list per XCD), the ids left over exit.  The
+// down projection skips the same (token tile, branch) pairs, and H is multiplied by the token's
+// route bit, so that it is exactly 0 where a token does not take a branch.
+template <int BMT, int WM, int NB, bool kRouted>
+__global__ void __launch_bounds__(WM * 128)
+gate_up_mfma(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
+             const uint16_t *__restrict__ Wu, uint16_t *__restrict__ H, int T, int d_model, int d_inter,
+             int ldh, int tiles_m, int tiles_n, const uint8_t *__restrict__ route, RouteTiles rt,
+             BranchTable bt)
+{
+    static_assert(!kRouted || BMT == BM, "the routed path's tables are per 256 tokens");
+    __shared__ __attribute__((aligned(1024))) char lds[lds_bytes(BMT, NB)];
+    constexpr int BNH = 32 * NB;                  // neurons per tile
+    int tm, tn;
+    if (kRouted) {
+        const int groups = (tiles_m + GROUP_M - 1) / GROUP_M;
+        int total = 0;
+        for (int g = 0; g < groups; ++g) total += (int)rt.counts[g];
+        const int per_xcd = ids_per_xcd(total);
+        const int k = blockIdx.x / XCDS;
+        const int logical = (blockIdx.x % XCDS) * per_xcd + k;
+        if (k >= per_xcd || logical >= total) return;
+        int g = 0, before = 0;
+        for (; g < groups - 1; ++g) {
+            const int c = (int)rt.counts[g];
+            if (logical < before + c) break;
+            before += c;
+        }
+        const int e = (int)rt.list[(size_t)g * rt.stride + (logical - before)];
+        const int m0 = g * GROUP_M;
+        const int gsz = tiles_m - m0 < GROUP_M ? tiles_m - m0 : GROUP_M;
+        tm = m0 + e % gsz;
+        tn = e / gsz;
+    } else if (!tile_of(blockIdx.x, tiles_m, tiles_n, tm, tn)) {
+        return;
+    }
+    int n0, n_end;
+    if (!neuron_tile(bt, tn, BNH, n0, n_end)) return;
+    gate_up_tile<BMT, WM, NB, kRouted>(X, Wg, Wu, H, T, d_model, ldh, route, bt, lds, tm, n0, n_end);
+}
+
+// The gate+up projection with WIDE tiles for the full rounds of 256 workgroups and NARROW tiles for what
+// is left, when that is at most half a round: the left-over wide tiles, cut in two, then fill one
+// (shorter) round of narrow tiles instead of leaving more than half of the CUs idle for a wide one.
+// Workgroup ids below 8 * wide_per_xcd take wide tiles: id i is tile (i % 8) * P + i / 8 of the grouped
+// order, P = ids_per_xcd(wide tiles), i.e. every XCD works through the first wide_per_xcd tiles of its
+// contiguous eighth.  The ids above take the rest of each eighth, two ids (halves of 64 neurons) per
+// wide tile.  grid.x = 8 * (wide_per_xcd + 2 * (P - wide_per_xcd)).
+template <int WM>
+__global__ void __launch_bounds__(WM * 128)
+gate_up_mfma_mixed(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
+                   const uint16_t *__restrict__ Wu, uint16_t *__restrict__ H, int T, int d_model, int ldh,
+                   int tiles_m, int tiles_n, int wide_per_xcd, BranchTable bt)
+{
+    __shared__ __attribute__((aligned(1024))) char lds[lds_bytes(BM, 4)];
+    const int total = tiles_m * tiles_n;
+    const int P = ids_per_xcd(total);
+    const int xcd = blockIdx.x % XCDS;
+    const int xcd_end = (xcd + 1) * P < total ? (xcd + 1) * P : total;
+    int k = blockIdx.x / XCDS;
+    int tm, tn, n0, n_end;
+    if (k < wide_per_xcd) {
+        const int logical = xcd * P + k;
+        if (logical >= xcd_end) return;
+        tile_from_logical(logical, tiles_m, tiles_n, tm, tn);
+        if (!neuron_tile(bt, tn, 128, n0, n_end)) return;
+        gate_up_tile<BM, WM, 4, false>(X, Wg, Wu, H, T, d_model, ldh, nullptr, bt, lds, tm, n0, n_end);
+    } else {
+        k -= wide_per_xcd;
+        const int logical = xcd * P + wide_per_xcd + k / 2;
+        if (logical >= xcd_end) return;
+        tile_from_logical(logical, tiles_m, tiles_n, tm, tn);
+        if (!neuron_tile(bt, tn, 128, n0, n_end)) return;
+        n0 += (k % 2) * 64;
+        if (n0 >= n_end) return;                                   // the run ends in the first half
+        gate_up_tile<BM, WM, 2, false>(X, Wg, Wu, H, T, d_model, ldh, nullptr, bt, lds, tm, n0, n_end);
+    }
+}
+
 // grid.x = splits * 8 * ids_per_xcd(tilesM * tilesN); dst = out (splits == 1) or partial[split][T][d_model].
-// dst_bf16 (only with splits == 1): dst holds bf16 values, each sum is rounded once (RNE).
+// dst_mode: DST_F32 plain float stores; DST_BF16 (only with splits == 1) dst holds bf16 values, each sum
+// rounded once (RNE).
 // kRouted: the K loop of token tile tm walks only the branches some token of the tile is routed
 // to (tile_need); H is 0 for the tokens of the tile that do not take a branch.
 template <int BMT, int WM, int NB, bool kRouted>
 __global__ void __launch_bounds__(WM * 128)
 down_mfma(const uint16_t *__restrict__ H, const uint16_t *__restrict__ Wd, float *__restrict__ dst, int T,
-          int d_model, int d_inter, int ldh, int tiles_m, int tiles_n, int splits, int kt_total, int dst_bf16,
+          int d_model, int d_inter, int ldh, int tiles_m, int tiles_n, int splits, int kt_total, int dst_mode,
           const uint8_t *__restrict__ tile_need, BranchTable bt)
 {
     static_assert(!kRouted || BMT == BM, "the routed path's tables are per 256 tokens");
@@ -584,7 +654,7 @@ down_mfma(const uint16_t *__restrict__ H, const uint16_t *__restrict__ Wd, float
                 // d_model is a multiple of 8: the four features are all inside or all outside
                 if (t < T && m < d_model) {
                     const f32x4 v = half ? acc1[i][j] : acc0[i][j];
-                    if (dst_bf16) {
+                    if (dst_mode == DST_BF16) {
                         u32x2 pk;
                         pk.x = (uint32_t)to_bf16(v[0]) | ((uint32_t)to_bf16(v[1]) << 16);
                         pk.y = (uint32_t)to_bf16(v[2]) | ((uint32_t)to_bf16(v[3]) << 16);
@@ -756,7 +826,9 @@ int k_tiles(const BranchTable &bt)
 // workgroups per CU: four times the tiles of WIDE, the fixed cost of one workgroup (first loads,
 // epilogue, hand-over) hidden under the main loop of the other, at 1.6 times WIDE's traffic into the
 // LDS per flop.  For layers and batches that give WIDE too few or too short tiles.
-enum TileShape { TILE_WIDE = 0, TILE_NARROW = 1, TILE_SMALL = 2 };
+// MIXED (gate+up only): WIDE for the full rounds of 256 workgroups, NARROW for a last round that WIDE tiles
+// would fill less than half.
+enum TileShape { TILE_WIDE = 0, TILE_NARROW = 1, TILE_SMALL = 2, TILE_MIXED = 3 };
 struct TileDims {
     int bm, bn;       // tokens, B rows per block (a tile has two blocks)
     int per_cu;       // workgroups resident per CU
@@ -771,32 +843,52 @@ long long gate_up_tiles(const BranchTable &bt, int T, TileShape sh)
     return n * ceil_div(T, kTileDims[sh].bm);
 }
 
-// Estimated duration of a launch of `tiles` tiles with nk K tiles each, in units of one K tile of a
-// WIDE tile.  Per K tile a NARROW tile costs 0.55 and a SMALL one 0.4 (two of them share a CU, each
-// at 0.2 of a WIDE tile's flops but bound by the traffic into the LDS); the fixed cost of a
-// workgroup is about 5 / 3.5 units, and about 1 for SMALL, whose neighbour on the CU computes meanwhile.
-double launch_cost(long long tiles, int nk, TileShape sh)
+// Estimated duration in microseconds of a launch of `tiles` tiles with nk K tiles each that streams
+// `bytes` of weights and activations, fitted to measurements on the two benchmark layers (T = 64 .. 4096):
+// a K tile of a WIDE tile takes about 1.48 us at the clocks the chip sustains on this work, a NARROW one
+// 0.62 of that, a SMALL one 0.4 (two share a CU, each at a quarter of a WIDE tile's flops but bound by the
+// traffic into the LDS; an odd one at the end runs alone at about 0.3); the fixed cost of a workgroup
+// (first loads, epilogue, hand-over) is about 7.4 / 5.2 us and 1.5 us for SMALL, whose neighbour on the CU
+// computes meanwhile.  A launch that has few tiles per CU cannot stream faster than about 3.5 TB/s.
+double launch_cost_us(long long tiles, int nk, TileShape sh, double bytes)
 {
-    static const double per_k[3] = {1.0, 0.55, 0.4}, fixed[3] = {5.0, 3.5, 1.0};
+    static const double per_k[3] = {1.48, 0.92, 0.59}, fixed[3] = {7.4, 5.2, 1.5};
     const long long per_cu = (tiles + kCUs - 1) / kCUs;       // tiles the busiest CU runs, one after the other
-    if (sh == TILE_SMALL) {
-        // two at a time: an odd one at the end runs alone, at its own speed (about 0.3 per K tile)
-        return (double)(per_cu / 2) * 2 * (nk * per_k[sh] + fixed[sh]) + (double)(per_cu % 2) * (nk * 0.3 + 3.0);
-    }
-    return (double)per_cu * (nk * per_k[sh] + fixed[sh]);
+    double c;
+    if (sh == TILE_SMALL)
+        c = (double)(per_cu / 2) * 2 * (nk * per_k[sh] + fixed[sh]) + (double)(per_cu % 2) * (nk * 0.44 + 4.4);
+    else
+        c = (double)per_cu * (nk * per_k[sh] + fixed[sh]);
+    return std::max(c, bytes / 3.5e6 + fixed[sh]);
+}
+
+// Wide tiles that MIXED runs as wide, per XCD (32 per full round of 256), or -1 if MIXED does not apply:
+// it needs at least one full round and a remainder of at most half a round.
+int mixed_wide_per_xcd(long long wide_tiles)
+{
+    const long long rounds = wide_tiles / kCUs, rest = wide_tiles % kCUs;
+    if (rounds < 1 || rest == 0 || rest > kCUs / 2 || wide_tiles > 0x3fffffffLL) return -1;
+    return (int)(rounds * (kCUs / XCDS));
 }
 
 TileShape pick_gate_up_tile(const BranchTable &bt, int T, int d_model)
 {
     const int nk = ceil_div(d_model, BK);
+    const double bytes = 4.0 * bt.d_eff * d_model;            // W_gate and W_up rows of the active neurons, once
+    const long long wide = gate_up_tiles(bt, T, TILE_WIDE);
     TileShape best = TILE_WIDE;
-    double best_cost = launch_cost(gate_up_tiles(bt, T, TILE_WIDE), nk, TILE_WIDE);
+    double best_cost = launch_cost_us(wide, nk, TILE_WIDE, bytes);
     for (TileShape sh : {TILE_NARROW, TILE_SMALL}) {
-        const double c = launch_cost(gate_up_tiles(bt, T, sh), nk, sh);
+        const double c = launch_cost_us(gate_up_tiles(bt, T, sh), nk, sh, bytes);
         if (c < best_cost * 0.97) {
             best = sh;
             best_cost = c;
         }
+    }
+    if (mixed_wide_per_xcd(wide) >= 0) {
+        // the full rounds as wide tiles, then one round of narrow ones
+        const double c = launch_cost_us(wide / kCUs * kCUs, nk, TILE_WIDE, 0.0) + launch_cost_us(kCUs, nk, TILE_NARROW, 0.0);
+        if (c < best_cost * 0.97) best = TILE_MIXED;
     }
     return best;
 }
@@ -813,22 +905,32 @@ int down_splits(int T, int d_model, int k_elems, TileShape sh)
     return s < 1 ? 1 : (int)s;
 }
 
-TileShape pick_down_tile(int T, int d_model, int k_elems)
+// How the down projection of one call is launched: tile shape and K split (the partial results of a split
+// go through the workspace and a second kernel adds them up in a fixed order; adding two halves into
+// the result with float atomics instead was measured 2.4 times slower on the 0.5B-shaped layer).
+struct DownPlan {
+    TileShape shape;
+    int splits;
+};
+
+DownPlan plan_down(const FwdArgs &a, const BranchTable &bt, bool routed)
 {
-    // the partial sums of a split K are written and read again: narrow tiles halve them
-    if (down_splits(T, d_model, k_elems, TILE_WIDE) == 1) return TILE_WIDE;
-    const int kt = ceil_div(k_elems > 0 ? k_elems : 1, BK);
-    TileShape best = TILE_NARROW;
+    const int kt = std::max(1, k_tiles(bt));
+    DownPlan best{TILE_WIDE, 1};
     double best_cost = 1e30;
-    for (TileShape sh : {TILE_NARROW, TILE_SMALL}) {
+    for (TileShape sh : {TILE_WIDE, TILE_NARROW, TILE_SMALL}) {
+        if (a.tile_shape >= 0 && a.tile_shape != (int)TILE_MIXED && a.tile_shape != (int)sh) continue;
+        if (routed && sh == TILE_SMALL) continue;
         const TileDims &d = kTileDims[sh];
-        const int sp = down_splits(T, d_model, k_elems, sh);
-        const long long tiles = (long long)ceil_div(T, d.bm) * ceil_div(d_model, 2 * d.bn) * sp;
-        // partial sums: sp * T * d_model floats written and read back, at about 3 TB/s; a unit is about 1.5 us
-        const double partial_units = sp > 1 ? 2.0 * sp * (double)T * d_model * 4.0 / 3e12 / 1.5e-6 : 0.0;
-        const double c = launch_cost(tiles, ceil_div(kt, sp), sh) + partial_units;
+        const long long tiles = (long long)ceil_div(a.T, d.bm) * ceil_div(a.d_model, 2 * d.bn);
+        int sp = std::min(down_splits(a.T, a.d_model, bt.d_eff, sh), kt);
+        if (sp > 1 && (size_t)sp * a.T * a.d_model * sizeof(float) > a.partial_bytes) sp = 1;
+        // split as far as it fills the chip; the second kernel that adds the sp partial sums up costs about
+        // 6 us plus (sp + 1) * T * d_model floats at 8 TB/s
+        double c = launch_cost_us(tiles * sp, ceil_div(kt, sp), sh, 2.0 * bt.d_eff * (a.d_model + a.T));
+        if (sp > 1) c += 6.0 + (sp + 1.0) * (double)a.T * a.d_model * 4.0 / 8e6;
         if (c < best_cost) {
-            best = sh;
+            best = DownPlan{sh, sp};
             best_cost = c;
         }
     }
@@ -899,6 +1001,22 @@ static hipError_t launch_gate_up(const FwdArgs &a, const BranchTable &bt)
     return launch_status("gate_up_mfma launch");
 }
 
+static hipError_t launch_gate_up_mixed(const FwdArgs &a, const BranchTable &bt)
+{
+    const int tiles_m = ceil_div(a.T, BM);
+    long long tiles_n = 0;
+    for (int r = 0; r < bt.n_runs; ++r) tiles_n += ceil_div(bt.run_end[r] - bt.run_start[r], BNH_MAX);
+    const int wide_per_xcd = mixed_wide_per_xcd(tiles_m * tiles_n);
+    if (wide_per_xcd < 0) return note_hip_error("gate_up_mfma_mixed: tile count", hipErrorInvalidValue);
+    const long long grid = (long long)XCDS * (wide_per_xcd + 2LL * (ids_per_xcd(tiles_m * tiles_n) - wide_per_xcd));
+    ProfileScope ps(MLPMOE_KERNEL_GATE_UP_MFMA, a.stream);
+    gate_up_mfma_mixed<MFMA_WM><<<(unsigned)grid, MFMA_WM * 128, 0, a.stream>>>(
+        static_cast<const uint16_t *>(a.x), static_cast<const uint16_t *>(a.Wg),
+        static_cast<const uint16_t *>(a.Wu), static_cast<uint16_t *>(a.H), a.T, a.d_model, a.ldh, tiles_m,
+        (int)tiles_n, wide_per_xcd, bt);
+    return launch_status("gate_up_mfma_mixed launch");
+}
+
 template <int BMT, int WM, int NB, bool kRouted = false>
 static hipError_t launch_down(const FwdArgs &a, const BranchTable &bt, int splits)
 {
@@ -909,32 +1027,27 @@ static hipError_t launch_down(const FwdArgs &a, const BranchTable &bt, int split
     if (grid > 0x7fffffffLL) return note_hip_error("down_mfma grid", hipErrorInvalidValue);
     ProfileScope ps(MLPMOE_KERNEL_DOWN_MFMA, a.stream);
     down_mfma<BMT, WM, NB, kRouted><<<(unsigned)grid, WM * 128, 0, a.stream>>>(
-        static_cast<const uint16_t *>(a.H), static_cast<const uint16_t *>(a.Wd), splits > 1 ? a.partial : a.out,
-        a.T, a.d_model, a.d_inter, a.ldh, tiles_m, tiles_n, splits, kt_total, (a.out_bf16 && splits == 1) ? 1 : 0,
-        a.route_scratch, bt);
+        static_cast<const uint16_t *>(a.H), static_cast<const uint16_t *>(a.Wd),
+        splits > 1 ? a.partial : a.out, a.T, a.d_model, a.d_inter, a.ldh, tiles_m, tiles_n, splits, kt_total,
+        (a.out_bf16 && splits == 1) ? DST_BF16 : DST_F32, a.route_scratch, bt);
     return launch_status("down_mfma launch");
 }
 
-// The down projection with the tile shape and K split chosen for the call, then the sum of the
-// partial results if K was split.  The split is taken from the active width (never more than the
-// workspace was sized for, d_inter >= d_eff) and never exceeds the K tiles there are.
+// The down projection as planned, then the sum of the partial results if K was split through the workspace.
 template <bool kRouted>
-static hipError_t down_and_reduce(const FwdArgs &a, const BranchTable &bt, TileShape sh)
+static hipError_t down_and_reduce(const FwdArgs &a, const BranchTable &bt, const DownPlan &pl)
 {
-    int splits = down_splits(a.T, a.d_model, bt.d_eff, sh);
-    splits = std::min(splits, std::max(1, k_tiles(bt)));
-    if (splits > 1 && (size_t)splits * a.T * a.d_model * sizeof(float) > a.partial_bytes) splits = 1;
     hipError_t e;
-    if (sh == TILE_WIDE) e = launch_down<BM, MFMA_WM, 4, kRouted>(a, bt, splits);
-    else if (sh == TILE_NARROW) e = launch_down<BM, MFMA_WM, 2, kRouted>(a, bt, splits);
-    else e = kRouted ? hipErrorInvalidValue : launch_down<BM_SMALL, SMALL_WM, 2, false>(a, bt, splits);
+    if (pl.shape == TILE_WIDE) e = launch_down<BM, MFMA_WM, 4, kRouted>(a, bt, pl.splits);
+    else if (pl.shape == TILE_NARROW) e = launch_down<BM, MFMA_WM, 2, kRouted>(a, bt, pl.splits);
+    else e = kRouted ? hipErrorInvalidValue : launch_down<BM_SMALL, SMALL_WM, 2, false>(a, bt, pl.splits);
     if (e != hipSuccess) return hipErrorLaunchFailure;
-    if (splits > 1) {
+    if (pl.splits > 1) {
         ProfileScope ps(MLPMOE_KERNEL_SPLITK_REDUCE, a.stream);
         const size_t n = (size_t)a.T * a.d_model;
         size_t blocks = (n + 255) / 256;
         if (blocks > 8192) blocks = 8192;
-        reduce_partials<<<(unsigned)blocks, 256, 0, a.stream>>>(a.partial, a.out, n, splits, a.out_bf16 ? 1 : 0);
+        reduce_partials<<<(unsigned)blocks, 256, 0, a.stream>>>(a.partial, a.out, n, pl.splits, a.out_bf16 ? 1 : 0);
     }
     return launch_status("reduce_partials launch");
 }
@@ -945,21 +1058,25 @@ hipError_t launch_mfma_routed_bf16(const FwdArgs &a, const BranchTable &bt)
 {
     hipError_t e = launch_gate_up<BM, MFMA_WM, 4, true>(a, bt);
     if (e != hipSuccess) return hipErrorLaunchFailure;
-    // 256-token tiles (the routing tables are per 256 tokens); narrow when K is split, as the
-    // unrouted launch did before it had other shapes to choose from
-    const bool narrow = down_splits(a.T, a.d_model, bt.d_eff, TILE_WIDE) > 1;
-    return down_and_reduce<true>(a, bt, narrow ? TILE_NARROW : TILE_WIDE);
+    // 256-token tiles (the routing tables are per 256 tokens); narrow when K is split: half the partial sums
+    int splits = down_splits(a.T, a.d_model, bt.d_eff, TILE_WIDE);
+    const TileShape sh = splits > 1 ? TILE_NARROW : TILE_WIDE;
+    splits = std::min(down_splits(a.T, a.d_model, bt.d_eff, sh), std::max(1, k_tiles(bt)));
+    if (splits > 1 && (size_t)splits * a.T * a.d_model * sizeof(float) > a.partial_bytes) splits = 1;
+    return down_and_reduce<true>(a, bt, DownPlan{sh, splits});
 }
 
 hipError_t launch_mfma_bf16(const FwdArgs &a, const BranchTable &bt)
 {
-    const TileShape gu = a.tile_shape >= 0 ? (TileShape)a.tile_shape : pick_gate_up_tile(bt, a.T, a.d_model);
+    const DownPlan pl = plan_down(a, bt, false);
+    TileShape gu = a.tile_shape >= 0 ? (TileShape)a.tile_shape : pick_gate_up_tile(bt, a.T, a.d_model);
+    if (gu == TILE_MIXED && mixed_wide_per_xcd(gate_up_tiles(bt, a.T, TILE_WIDE)) < 0) gu = TILE_WIDE;   // forced where it does not apply
     hipError_t e = gu == TILE_WIDE     ? launch_gate_up<BM, MFMA_WM, 4>(a, bt)
                    : gu == TILE_NARROW ? launch_gate_up<BM, MFMA_WM, 2>(a, bt)
-                                       : launch_gate_up<BM_SMALL, SMALL_WM, 2>(a, bt);
+                   : gu == TILE_SMALL  ? launch_gate_up<BM_SMALL, SMALL_WM, 2>(a, bt)
+                                       : launch_gate_up_mixed(a, bt);
     if (e != hipSuccess) return hipErrorLaunchFailure;
-    return down_and_reduce<false>(a, bt, a.tile_shape >= 0 ? (TileShape)a.tile_shape
-                                                              : pick_down_tile(a.T, a.d_model, bt.d_eff));
+    return down_and_reduce<false>(a, bt, pl);
 }
 
 }  // namespace mlpmoe

@@ -323,6 +323,28 @@ def test_first_k_sweep(mm, K):
     check_bf16_flip_aware(got, H, *a1, label="first-K K=%d T=1:" % K)
 
 
+def test_bf16_mfma_mixed_tile_widths(mm):
+    """More than one round of 256 wide tiles with a small remainder: the gate+up launch runs the full round
+    with 256 x (128 + 128) tiles and the remainder as halves of 64 neurons.  Ten token tiles (the last ragged),
+    three runs of active branches whose last wide tiles are 104, 88 and exactly 64 neurons wide (a second
+    half that is partly filled, and one that is empty)."""
+    widths = [1000, 200, 1640, 1008, 8, 192]
+    off = np.concatenate([[0], np.cumsum(widths)]).astype(np.int32)
+    mask = [1, 0, 1, 1, 0, 1]
+    args = small_bf16_case(77, 2304 + 77, 64, off.tolist(), mask)
+    got, H = run_gpu_with_hidden(*args, path=mm.PATH_MFMA_MIXED)
+    e_c, _, _ = check_bf16_flip_aware(got, H, *args, label="mixed tile widths:")
+    assert e_c <= BF16_TOL                                 # the plain gate as well (3840 active neurons)
+    # every output element adds up the same products in the same order whatever the tile width
+    wide, Hw = run_gpu_with_hidden(*args, path=mm.PATH_MFMA_WIDE)
+    act = np.repeat(np.array(mask, bool), widths)
+    assert np.array_equal(H[:, act], Hw[:, act])
+    assert np.array_equal(got, run_gpu(*args, path=mm.PATH_MFMA_MIXED))
+    # where the tile count leaves no such remainder the selector falls back to wide tiles
+    small = small_bf16_case(78, 300, 64, [0, 1024], [1])
+    assert np.array_equal(run_gpu(*small, path=mm.PATH_MFMA_MIXED), run_gpu(*small, path=mm.PATH_MFMA_WIDE))
+
+
 THIN_CASES = [
     # active neurons from 8 to 512: one thin branch of a faded or pruned layer.  T, d_model, offsets, mask
     (300, 136, [0, 8], [1]),

@@ -26,7 +26,11 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
-constexpr int KB = 64;   // K elements per wave step: two MFMA steps, 32 contiguous bytes per lane
+constexpr int KB = 64;   // K elements per wave step: two MFMA steps of 32
+// Which 8 of a block's 64 K elements a lane feeds to the two MFMA steps: group q = lane >> 4 takes elements
+// q * KQ .. + 7 for the first step and q * KQ + KH .. + 7 for the second.  Any assignment works as long as x
+// is loaded the same way (the dot product does not care about the order of K).
+constexpr int KQ = 16, KH = 8;
 
 // 16 zero bytes: lanes with nothing to load (token >= T, K chunk past the end of a range) read here.
 __device__ const uint32_t g_zero16[4] = {0, 0, 0, 0};
@@ -144,9 +148,9 @@ decode_kernel(const uint16_t *__restrict__ Xin, int ldx, int T,
         m = m < d_model ? m : d_model - 1;               // clamped rows are computed but never stored
         wrow = W0 + (size_t)m * ldw;
     }
-    wrow += q * 16;
+    wrow += q * KQ;
     const bool tok = r16 < T;
-    const uint16_t *xp = Xin + (size_t)(tok ? r16 : 0) * ldx + q * 16;
+    const uint16_t *xp = Xin + (size_t)(tok ? r16 : 0) * ldx + q * KQ;
     const uint16_t *zero = reinterpret_cast<const uint16_t *>(g_zero16);
 
     // cursor over this wave's blocks: (range, block inside the range); ranges laid end to end
@@ -179,12 +183,12 @@ decode_kernel(const uint16_t *__restrict__ Xin, int ldx, int T,
         const bool live = cr < n_ranges;
         const int k = live ? rbeg(cr) + cb * KB : 0;
         const int kend = live ? rend(cr) : -1;
-        const int kl = k + q * 16;
-        const bool ok0 = kl < kend, ok1 = kl + 8 < kend;
+        const int kl = k + q * KQ;
+        const bool ok0 = kl < kend, ok1 = kl + KH < kend;
         wa[u][0] = ld16(ok0 ? wrow + k : zero);
-        wa[u][1] = ld16(ok1 ? wrow + k + 8 : zero);
+        wa[u][1] = ld16(ok1 ? wrow + k + KH : zero);
         xa[u][0] = ld16((ok0 && tok) ? xp + k : zero);
-        xa[u][1] = ld16((ok1 && tok) ? xp + k + 8 : zero);
+        xa[u][1] = ld16((ok1 && tok) ? xp + k + KH : zero);
         cb += NW;
         settle();
     };
@@ -264,10 +268,10 @@ decode_down_split(const uint16_t *__restrict__ Hin, int ldx, int T, const uint16
     for (int rt = 0; rt < RT; ++rt) {
         int m = row0 + rt * 16 + r16;
         m = m < d_model ? m : d_model - 1;               // clamped rows are computed but never stored
-        wrow[rt] = Wd + (size_t)m * ldw + q * 16;
+        wrow[rt] = Wd + (size_t)m * ldw + q * KQ;
     }
     const bool tok = r16 < T;
-    const uint16_t *xp = Hin + (size_t)(tok ? r16 : 0) * ldx + q * 16;
+    const uint16_t *xp = Hin + (size_t)(tok ? r16 : 0) * ldx + q * KQ;
     const uint16_t *zero = reinterpret_cast<const uint16_t *>(g_zero16);
 
     // cursor over this wave's blocks.  The K blocks of all ranges, laid end to end, are cut into KS
@@ -298,15 +302,15 @@ decode_down_split(const uint16_t *__restrict__ Hin, int ldx, int T, const uint16
         ++issued;
         const int k = live ? st.beg(cr) + cb * KB : 0;
         const int kend = live ? st.end(cr) : -1;
-        const int kl = k + q * 16;
-        const bool ok0 = kl < kend, ok1 = kl + 8 < kend;
+        const int kl = k + q * KQ;
+        const bool ok0 = kl < kend, ok1 = kl + KH < kend;
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
             wa[u][rt][0] = ld16(ok0 ? wrow[rt] + k : zero);
-            wa[u][rt][1] = ld16(ok1 ? wrow[rt] + k + 8 : zero);
+            wa[u][rt][1] = ld16(ok1 ? wrow[rt] + k + KH : zero);
         }
         xa[u][0] = ld16((ok0 && tok) ? xp + k : zero);
-        xa[u][1] = ld16((ok1 && tok) ? xp + k + 8 : zero);
+        xa[u][1] = ld16((ok1 && tok) ? xp + k + KH : zero);
         cb += stride;
         settle();
     };
@@ -378,11 +382,11 @@ decode_gate_up_persist(const uint16_t *__restrict__ X, int T, const uint16_t *__
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int r16 = lane & 15, q = lane >> 4;
     const bool tok = r16 < T;
-    const int x_lane = (tok ? r16 : 0) * row_bytes + q * 32;
+    const int x_lane = (tok ? r16 : 0) * row_bytes + q * (KQ * 2);
     const uint16_t *zero = reinterpret_cast<const uint16_t *>(g_zero16);
     const int nblk = (d_model + KB - 1) / KB;
     const int nb_pad = ((nblk + NW - 1) / NW + U - 1) / U * U;    // blocks per wave per tile, padded
-    const size_t lane_row_off = (size_t)(r16 & 7) * d_model + q * 16;
+    const size_t lane_row_off = (size_t)(r16 & 7) * d_model + q * KQ;
     const uint16_t *wsel = r16 < 8 ? Wg : Wu;
 
     // with routing the workgroups share out the tiles of the live branches only
@@ -396,10 +400,10 @@ decode_gate_up_persist(const uint16_t *__restrict__ X, int T, const uint16_t *__
     u32x4 wa[U][2];
     auto load_next = [&](int u) {
         const int b = wave + NW * l_j;                   // K block inside the tile
-        const int kl = b * KB + q * 16;
+        const int kl = b * KB + q * KQ;
         const bool more = l_row0 >= 0;
         wa[u][0] = ld16((more && kl < d_model) ? l_wrow + b * KB : zero);
-        wa[u][1] = ld16((more && kl + 8 < d_model) ? l_wrow + b * KB + 8 : zero);
+        wa[u][1] = ld16((more && kl + KH < d_model) ? l_wrow + b * KB + KH : zero);
         if (++l_j == nb_pad) {
             l_j = 0;
             l_cur.advance(st, gridDim.x);
@@ -441,9 +445,9 @@ decode_gate_up_persist(const uint16_t *__restrict__ X, int T, const uint16_t *__
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int b = wave + NW * (j0 + u);
-                const int kl = b * KB + q * 16;
+                const int kl = b * KB + q * KQ;
                 const int xo0 = (tok && kl < d_model) ? x_lane + b * (KB * 2) : zero_off;
-                const int xo1 = (tok && kl + 8 < d_model) ? x_lane + b * (KB * 2) + 16 : zero_off;
+                const int xo1 = (tok && kl + KH < d_model) ? x_lane + b * (KB * 2) + KH * 2 : zero_off;
                 const bf16x8 x0 = *reinterpret_cast<const bf16x8 *>(xs + xo0);
                 const bf16x8 x1 = *reinterpret_cast<const bf16x8 *>(xs + xo1);
                 acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(wa[u][0]), x0, acc, 0, 0, 0);
@@ -499,7 +503,7 @@ decode_gate_up_xreg(const uint16_t *__restrict__ X, int T, const uint16_t *__res
     const int r16 = lane & 15, q = lane >> 4;
     const bool tok = r16 < T;
     const uint16_t *zero = reinterpret_cast<const uint16_t *>(g_zero16);
-    const size_t lane_row_off = (size_t)(r16 & 7) * d_model + q * 16;
+    const size_t lane_row_off = (size_t)(r16 & 7) * d_model + q * KQ;
     const uint16_t *wsel = r16 < 8 ? Wg : Wu;
     const Stretches<kRouted> st{bt, kRouted ? live_branches(bt, route, T) : 0ULL};
 
@@ -510,10 +514,10 @@ decode_gate_up_xreg(const uint16_t *__restrict__ X, int T, const uint16_t *__res
     u32x4 wa[U][2];
     auto load_next = [&](int u) {
         const int b = wave + NW * l_j;
-        const int kl = b * KB + q * 16;
+        const int kl = b * KB + q * KQ;
         const bool more = l_row0 >= 0;
         wa[u][0] = ld16((more && kl < d_model) ? l_wrow + b * KB : zero);
-        wa[u][1] = ld16((more && kl + 8 < d_model) ? l_wrow + b * KB + 8 : zero);
+        wa[u][1] = ld16((more && kl + KH < d_model) ? l_wrow + b * KB + KH : zero);
         if (++l_j == XB) {
             l_j = 0;
             l_cur.advance(st, gridDim.x);
@@ -527,13 +531,13 @@ decode_gate_up_xreg(const uint16_t *__restrict__ X, int T, const uint16_t *__res
     // this wave's x fragments, once
     u32x4 xr[XB][2];
     {
-        const uint16_t *xp = X + (size_t)(tok ? r16 : 0) * d_model + q * 16;
+        const uint16_t *xp = X + (size_t)(tok ? r16 : 0) * d_model + q * KQ;
 #pragma unroll
         for (int j = 0; j < XB; ++j) {
             const int b = wave + NW * j;
-            const int kl = b * KB + q * 16;
+            const int kl = b * KB + q * KQ;
             xr[j][0] = ld16((tok && kl < d_model) ? xp + b * KB : zero);
-            xr[j][1] = ld16((tok && kl + 8 < d_model) ? xp + b * KB + 8 : zero);
+            xr[j][1] = ld16((tok && kl + KH < d_model) ? xp + b * KB + KH : zero);
         }
     }
 
@@ -643,7 +647,7 @@ static hipError_t launch_decode_impl(const FwdArgs &a, const BranchTable &bt)
     }
     ProfileScope ps(MLPMOE_KERNEL_DECODE_DOWN, a.stream);
     if (split_down)
-        decode_down_split<8, 4, kRouted><<<dim3(ceil_div(a.d_model, 32), 2), 8 * 64, 0, a.stream>>>(
+        decode_down_split<4, 8, kRouted><<<dim3(ceil_div(a.d_model, 32), 2), 4 * 64, 0, a.stream>>>(
             H, a.ldh, a.T, static_cast<const uint16_t *>(a.Wd), a.d_inter, a.d_model, a.out, a.route, bt);
     else if (tiles2 >= 192)
         decode_kernel<DEC_NW2, DEC_U2, false, kRouted><<<tiles2, DEC_NW2 * 64, 0, a.stream>>>(

@@ -30,12 +30,14 @@ constexpr int BM = 256;          // tokens per tile of the large-tile kernels (a
 constexpr int BM_SMALL = 128;    // tokens per tile of the small-tile kernels
 constexpr int BNH_MAX = 128;     // rows of each of the two B blocks: 32 * NB, NB = 4 (128) or 2 (64)
 constexpr int BK = 64;           // K elements per tile: one tile row is 128 bytes = one cache line
-constexpr int N_PARTS = 5;                           // ring of parts: A0 B0 A1 B1 A2 | B2 A3 ...
+// The LDS is a ring of 2 D + 1 parts, D = K tiles requested ahead of the one in use (A0 B0 A1 B1 A2 | B2 A3 ...
+// for D = 2, the depth of the 256-token tiles, whose ring then fills the LDS of a CU).
+__host__ __device__ constexpr int n_parts(int depth) { return 2 * depth + 1; }
 // A part of the ring holds the A rows (BMT tokens), or the B rows (2 blocks of 32 NB), of one K tile.
 // 256-token tiles: 32 KiB parts, the ring is the whole LDS of a CU (one workgroup of 8 waves per CU).
 // 128-token tiles with NB = 2: 16 KiB parts, 80 KiB per workgroup of 4 waves, two workgroups per CU.
 __host__ __device__ constexpr int part_bytes(int bmt, int nb) { return (bmt > 64 * nb ? bmt : 64 * nb) * BK * 2; }
-__host__ __device__ constexpr int lds_bytes(int bmt, int nb) { return N_PARTS * part_bytes(bmt, nb); }
+__host__ __device__ constexpr int lds_bytes(int bmt, int nb, int depth = 2) { return n_parts(depth) * part_bytes(bmt, nb); }
 constexpr int MFMA_WM = 4;                           // waves along M of the 256-token tiles: 8 waves of 64 x (64+64) outputs
 constexpr int SMALL_WM = 2;                          // ... of the 128-token tiles: 4 waves of 64 x (32+32)
 
@@ -161,7 +163,7 @@ __device__ __forceinline__ KCursor k_seek(const KR &kr, int tile)
 // NB = 16-row MFMA pieces per B block per wave: 4 (B blocks of 128 rows, a 256 x 256 tile) or 2 (B
 // blocks of 64 rows, a 256 x 128 tile, for shapes that would otherwise leave most CUs without a
 // tile in the last round).  A B part of 64 + 64 rows fills half of its ring slot.
-template <int BMT, int WM, int NB, bool kRowsAreB, typename KR>
+template <int BMT, int WM, int NB, int D, bool kRowsAreB, typename KR>
 __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, int lda, int a_valid,
                                          const uint16_t *__restrict__ B0_tile,
                                          const uint16_t *__restrict__ B1_tile, int ldb, int b0_valid,
@@ -176,6 +178,8 @@ __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, in
     constexpr int N_SLOTS = MI * NB / 2;          // slots of 4 MFMAs per K step
     constexpr int N_PIECES = 2 * NB + MI;         // fragment pieces per K step
     constexpr int PART_BYTES = part_bytes(BMT, NB);
+    constexpr int N_PARTS = n_parts(D);
+    static_assert(D >= 2, "one tile in use, at least one more on its way");
     static_assert(N_SLOTS % PL == 0 && N_SLOTS % PLB == 0 && PL % 2 == 0 && PLB % 2 == 0,
                   "loads spread evenly over the slots, slab parity is load parity");
     static_assert(2 * N_SLOTS >= N_PIECES, "two fragment reads per slot cover a K step");
@@ -321,7 +325,7 @@ __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, in
         }
     };
 
-    // prologue: parts A0 B0 A1 B1 in flight, tile 0 landed
+    // prologue: the parts of tiles 0 .. D-1 in flight, tile 0 landed
     Issue qa, qb;
     {
         const KCursor c = k_seek(kr, kt_begin);
@@ -334,7 +338,7 @@ __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, in
         qb.slot = 1;
     }
 #pragma unroll
-    for (int p = 0; p < 2; ++p) {
+    for (int p = 0; p < D; ++p) {
         const Part pa = part_of(qa, a_base, wa_dst), pb = part_of(qb, b_base, wb_dst);
 #pragma unroll
         for (int n = 0; n < PL; ++n) dma_part(n, pa, a_off);
@@ -343,7 +347,7 @@ __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, in
         advance(qa);
         advance(qb);
     }
-    pipeline_barrier<PL + PLB>();
+    pipeline_barrier<(D - 1) * (PL + PLB)>();
     Frags f0, f1;
 #pragma unroll
     for (int g = 0; g < N_PIECES; ++g) read_piece(f0, g, 0, 0);
@@ -351,12 +355,13 @@ __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, in
     int rd = 0;                                   // ring slot of the A part of the tile in use
     for (int it = 0; it < nk; ++it) {
         const Part pa = part_of(qa, a_base, wa_dst);
-        k_step(f0, f1, rd, 1, 1, pa);             // + A part of tile it+2
+        k_step(f0, f1, rd, 1, 1, pa);             // + A part of tile it+D
         advance(qa);
-        pipeline_barrier<PL>();                   // tile it+1 has landed; tile it's slots are free
+        // tile it+1 has landed (the newer tiles and the A part just issued may be in flight); tile it's slots are free
+        pipeline_barrier<(D - 2) * (PL + PLB) + PL>();
         rd = rd + 2 < N_PARTS ? rd + 2 : rd + 2 - N_PARTS;
         const Part pb = part_of(qb, b_base, wb_dst);
-        k_step(f1, f0, rd, 0, 2, pb);             // + B part of tile it+2
+        k_step(f1, f0, rd, 0, 2, pb);             // + B part of tile it+D
         advance(qb);
     }
     pipeline_barrier<0>();                        // LDS may be reused by the caller
@@ -444,8 +449,8 @@ __device__ __forceinline__ bool neuron_tile(const BranchTable &bt, int tn, int b
 }
 
 // One tile of the gate+up projection: tokens tm * BMT .., neurons n0 .. min(n0 + 32 NB, n_end) of a run that
-// ends at n_end.  lds: lds_bytes(BMT, NB) bytes.
-template <int BMT, int WM, int NB, bool kRouted>
+// ends at n_end.  lds: lds_bytes(BMT, NB, D) bytes.
+template <int BMT, int WM, int NB, int D, bool kRouted>
 __device__ __forceinline__ void gate_up_tile(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
                                              const uint16_t *__restrict__ Wu, uint16_t *__restrict__ H, int T,
                                              int d_model, int ldh, const uint8_t *__restrict__ route,
@@ -465,7 +470,7 @@ __device__ __forceinline__ void gate_up_tile(const uint16_t *__restrict__ X, con
         }
 
     const int nk = (d_model + BK - 1) / BK;
-    mainloop<BMT, WM, NB, true>(X + (size_t)t0 * d_model, d_model, T - t0, Wg + (size_t)n0 * d_model,
+    mainloop<BMT, WM, NB, D, true>(X + (size_t)t0 * d_model, d_model, T - t0, Wg + (size_t)n0 * d_model,
                        Wu + (size_t)n0 * d_model, d_model, n_end - n0, n_end - n0, KSingle{d_model}, 0, nk,
                        lds, accg, accu);
 
@@ -514,7 +519,7 @@ __device__ __forceinline__ void gate_up_tile(const uint16_t *__restrict__ X, con
 // over the full grid (one contiguous stretch of the list per XCD), the ids left over exit.  The
 // down projection skips the same (token tile, branch) pairs, and H is multiplied by the token's
 // route bit, so that it is exactly 0 where a token does not take a branch.
-template <int BMT, int WM, int NB, bool kRouted>
+template <int BMT, int WM, int NB, int D, bool kRouted>
 __global__ void __launch_bounds__(WM * 128)
 gate_up_mfma(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
              const uint16_t *__restrict__ Wu, uint16_t *__restrict__ H, int T, int d_model, int d_inter,
@@ -522,7 +527,7 @@ gate_up_mfma(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
              BranchTable bt)
 {
     static_assert(!kRouted || BMT == BM, "the routed path's tables are per 256 tokens");
-    __shared__ __attribute__((aligned(1024))) char lds[lds_bytes(BMT, NB)];
+    __shared__ __attribute__((aligned(1024))) char lds[lds_bytes(BMT, NB, D)];
     constexpr int BNH = 32 * NB;                  // neurons per tile
     int tm, tn;
     if (kRouted) {
@@ -549,7 +554,7 @@ gate_up_mfma(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
     }
     int n0, n_end;
     if (!neuron_tile(bt, tn, BNH, n0, n_end)) return;
-    gate_up_tile<BMT, WM, NB, kRouted>(X, Wg, Wu, H, T, d_model, ldh, route, bt, lds, tm, n0, n_end);
+    gate_up_tile<BMT, WM, NB, D, kRouted>(X, Wg, Wu, H, T, d_model, ldh, route, bt, lds, tm, n0, n_end);
 }
 
 // The gate+up projection with WIDE tiles for the full rounds of 256 workgroups and NARROW tiles for what
@@ -577,7 +582,7 @@ gate_up_mfma_mixed(const uint16_t *__restrict__ X, const uint16_t *__restrict__ 
         if (logical >= xcd_end) return;
         tile_from_logical(logical, tiles_m, tiles_n, tm, tn);
         if (!neuron_tile(bt, tn, 128, n0, n_end)) return;
-        gate_up_tile<BM, WM, 4, false>(X, Wg, Wu, H, T, d_model, ldh, nullptr, bt, lds, tm, n0, n_end);
+        gate_up_tile<BM, WM, 4, 2, false>(X, Wg, Wu, H, T, d_model, ldh, nullptr, bt, lds, tm, n0, n_end);
     } else {
         k -= wide_per_xcd;
         const int logical = xcd * P + wide_per_xcd + k / 2;
@@ -586,7 +591,7 @@ gate_up_mfma_mixed(const uint16_t *__restrict__ X, const uint16_t *__restrict__ 
         if (!neuron_tile(bt, tn, 128, n0, n_end)) return;
         n0 += (k % 2) * 64;
         if (n0 >= n_end) return;                                   // the run ends in the first half
-        gate_up_tile<BM, WM, 2, false>(X, Wg, Wu, H, T, d_model, ldh, nullptr, bt, lds, tm, n0, n_end);
+        gate_up_tile<BM, WM, 2, 2, false>(X, Wg, Wu, H, T, d_model, ldh, nullptr, bt, lds, tm, n0, n_end);
     }
 }
 
@@ -595,14 +600,14 @@ gate_up_mfma_mixed(const uint16_t *__restrict__ X, const uint16_t *__restrict__ 
 // rounded once (RNE).
 // kRouted: the K loop of token tile tm walks only the branches some token of the tile is routed
 // to (tile_need); H is 0 for the tokens of the tile that do not take a branch.
-template <int BMT, int WM, int NB, bool kRouted>
+template <int BMT, int WM, int NB, int D, bool kRouted>
 __global__ void __launch_bounds__(WM * 128)
 down_mfma(const uint16_t *__restrict__ H, const uint16_t *__restrict__ Wd, float *__restrict__ dst, int T,
           int d_model, int d_inter, int ldh, int tiles_m, int tiles_n, int splits, int kt_total, int dst_mode,
           const uint8_t *__restrict__ tile_need, BranchTable bt)
 {
     static_assert(!kRouted || BMT == BM, "the routed path's tables are per 256 tokens");
-    __shared__ __attribute__((aligned(1024))) char lds[lds_bytes(BMT, NB)];
+    __shared__ __attribute__((aligned(1024))) char lds[lds_bytes(BMT, NB, D)];
     const int per_split = XCDS * ids_per_xcd((long long)tiles_m * tiles_n);
     const int z = blockIdx.x / per_split;
     int tm, tn;
@@ -631,11 +636,11 @@ down_mfma(const uint16_t *__restrict__ H, const uint16_t *__restrict__ Wd, float
     // the second block of output features may start past d_model: point it at the last row
     const int n1 = n0 + BNH < d_model ? n0 + BNH : d_model - 1;
     if (kRouted)
-        mainloop<BMT, WM, NB, true>(H + (size_t)t0 * ldh, ldh, T - t0, Wd + (size_t)n0 * d_inter,
+        mainloop<BMT, WM, NB, D, true>(H + (size_t)t0 * ldh, ldh, T - t0, Wd + (size_t)n0 * d_inter,
                                     Wd + (size_t)n1 * d_inter, d_inter, d_model - n0, d_model - n1, dyn, kt_begin,
                                     kt_end, lds, acc0, acc1);
     else
-        mainloop<BMT, WM, NB, true>(H + (size_t)t0 * ldh, ldh, T - t0, Wd + (size_t)n0 * d_inter,
+        mainloop<BMT, WM, NB, D, true>(H + (size_t)t0 * ldh, ldh, T - t0, Wd + (size_t)n0 * d_inter,
                                     Wd + (size_t)n1 * d_inter, d_inter, d_model - n0, d_model - n1, KRuns{bt},
                                     kt_begin, kt_end, lds, acc0, acc1);
 
@@ -828,12 +833,16 @@ int k_tiles(const BranchTable &bt)
 // LDS per flop.  For layers and batches that give WIDE too few or too short tiles.
 // MIXED (gate+up only): WIDE for the full rounds of 256 workgroups, NARROW for a last round that WIDE tiles
 // would fill less than half.
-enum TileShape { TILE_WIDE = 0, TILE_NARROW = 1, TILE_SMALL = 2, TILE_MIXED = 3 };
+// DEEP: SMALL's tile with four K tiles requested ahead instead of two (a ring of 9 parts, 144 KiB, one
+// workgroup per CU): for batches of a few dozen to a hundred tokens, where a launch has about one tile per
+// CU and is bound by how many bytes of weights it keeps in flight, not by the matrix cores.
+enum TileShape { TILE_WIDE = 0, TILE_NARROW = 1, TILE_SMALL = 2, TILE_MIXED = 3, TILE_DEEP = 4 };
+constexpr int DEEP_D = 4;
 struct TileDims {
     int bm, bn;       // tokens, B rows per block (a tile has two blocks)
     int per_cu;       // workgroups resident per CU
 };
-constexpr TileDims kTileDims[3] = {{BM, 128, 1}, {BM, 64, 1}, {BM_SMALL, 64, 2}};
+constexpr TileDims kTileDims[5] = {{BM, 128, 1}, {BM, 64, 1}, {BM_SMALL, 64, 2}, {BM, 128, 1}, {BM_SMALL, 64, 1}};
 constexpr int kCUs = 256;
 
 long long gate_up_tiles(const BranchTable &bt, int T, TileShape sh)
@@ -849,17 +858,20 @@ long long gate_up_tiles(const BranchTable &bt, int T, TileShape sh)
 // 0.62 of that, a SMALL one 0.4 (two share a CU, each at a quarter of a WIDE tile's flops but bound by the
 // traffic into the LDS; an odd one at the end runs alone at about 0.3); the fixed cost of a workgroup
 // (first loads, epilogue, hand-over) is about 7.4 / 5.2 us and 1.5 us for SMALL, whose neighbour on the CU
-// computes meanwhile.  A launch that has few tiles per CU cannot stream faster than about 3.5 TB/s.
+// computes meanwhile; DEEP (SMALL's tile alone on its CU) 0.75 and 4.4 us.  A launch that has few tiles per CU
+// cannot stream faster than about 3.5 TB/s, 5 TB/s with DEEP's longer queue of requests.
+constexpr double kDeepStreamBytesPerUs = 5.0e6;
 double launch_cost_us(long long tiles, int nk, TileShape sh, double bytes)
 {
-    static const double per_k[3] = {1.48, 0.92, 0.59}, fixed[3] = {7.4, 5.2, 1.5};
+    static const double per_k[5] = {1.48, 0.92, 0.59, 1.48, 0.75}, fixed[5] = {7.4, 5.2, 1.5, 7.4, 4.4};
     const long long per_cu = (tiles + kCUs - 1) / kCUs;       // tiles the busiest CU runs, one after the other
     double c;
     if (sh == TILE_SMALL)
         c = (double)(per_cu / 2) * 2 * (nk * per_k[sh] + fixed[sh]) + (double)(per_cu % 2) * (nk * 0.44 + 4.4);
     else
         c = (double)per_cu * (nk * per_k[sh] + fixed[sh]);
-    return std::max(c, bytes / 3.5e6 + fixed[sh]);
+    // DEEP keeps twice the bytes in flight
+    return std::max(c, bytes / (sh == TILE_DEEP ? kDeepStreamBytesPerUs : 3.5e6) + fixed[sh]);
 }
 
 // Wide tiles that MIXED runs as wide, per XCD (32 per full round of 256), or -1 if MIXED does not apply:
@@ -878,7 +890,7 @@ TileShape pick_gate_up_tile(const BranchTable &bt, int T, int d_model)
     const long long wide = gate_up_tiles(bt, T, TILE_WIDE);
     TileShape best = TILE_WIDE;
     double best_cost = launch_cost_us(wide, nk, TILE_WIDE, bytes);
-    for (TileShape sh : {TILE_NARROW, TILE_SMALL}) {
+    for (TileShape sh : {TILE_NARROW, TILE_SMALL, TILE_DEEP}) {
         const double c = launch_cost_us(gate_up_tiles(bt, T, sh), nk, sh, bytes);
         if (c < best_cost * 0.97) {
             best = sh;
@@ -918,9 +930,9 @@ DownPlan plan_down(const FwdArgs &a, const BranchTable &bt, bool routed)
     const int kt = std::max(1, k_tiles(bt));
     DownPlan best{TILE_WIDE, 1};
     double best_cost = 1e30;
-    for (TileShape sh : {TILE_WIDE, TILE_NARROW, TILE_SMALL}) {
+    for (TileShape sh : {TILE_WIDE, TILE_NARROW, TILE_SMALL, TILE_DEEP}) {
         if (a.tile_shape >= 0 && a.tile_shape != (int)TILE_MIXED && a.tile_shape != (int)sh) continue;
-        if (routed && sh == TILE_SMALL) continue;
+        if (routed && (sh == TILE_SMALL || sh == TILE_DEEP)) continue;
         const TileDims &d = kTileDims[sh];
         const long long tiles = (long long)ceil_div(a.T, d.bm) * ceil_div(a.d_model, 2 * d.bn);
         int sp = std::min(down_splits(a.T, a.d_model, bt.d_eff, sh), kt);
@@ -963,11 +975,11 @@ size_t mfma_partial_bytes(int T, int d_model, int d_inter)
 {
     // the largest any tile shape asks for
     int s = 1;
-    for (TileShape sh : {TILE_WIDE, TILE_NARROW, TILE_SMALL}) s = std::max(s, down_splits(T, d_model, d_inter, sh));
+    for (TileShape sh : {TILE_WIDE, TILE_NARROW, TILE_SMALL, TILE_DEEP}) s = std::max(s, down_splits(T, d_model, d_inter, sh));
     return s > 1 ? align_up((size_t)s * T * d_model * sizeof(float), 256) : 0;
 }
 
-template <int BMT, int WM, int NB, bool kRouted = false>
+template <int BMT, int WM, int NB, int D = 2, bool kRouted = false>
 static hipError_t launch_gate_up(const FwdArgs &a, const BranchTable &bt)
 {
     const int tiles_m = ceil_div(a.T, BMT);
@@ -994,7 +1006,7 @@ static hipError_t launch_gate_up(const FwdArgs &a, const BranchTable &bt)
         rt = RouteTiles{need, counts, list, stride};
     }
     ProfileScope ps(MLPMOE_KERNEL_GATE_UP_MFMA, a.stream);
-    gate_up_mfma<BMT, WM, NB, kRouted><<<(unsigned)grid, WM * 128, 0, a.stream>>>(
+    gate_up_mfma<BMT, WM, NB, D, kRouted><<<(unsigned)grid, WM * 128, 0, a.stream>>>(
         static_cast<const uint16_t *>(a.x), static_cast<const uint16_t *>(a.Wg),
         static_cast<const uint16_t *>(a.Wu), static_cast<uint16_t *>(a.H), a.T, a.d_model, a.d_inter,
         a.ldh, tiles_m, (int)tiles_n, a.route, rt, bt);
@@ -1017,7 +1029,7 @@ static hipError_t launch_gate_up_mixed(const FwdArgs &a, const BranchTable &bt)
     return launch_status("gate_up_mfma_mixed launch");
 }
 
-template <int BMT, int WM, int NB, bool kRouted = false>
+template <int BMT, int WM, int NB, int D = 2, bool kRouted = false>
 static hipError_t launch_down(const FwdArgs &a, const BranchTable &bt, int splits)
 {
     const int tiles_m = ceil_div(a.T, BMT);
@@ -1026,7 +1038,7 @@ static hipError_t launch_down(const FwdArgs &a, const BranchTable &bt, int split
     const long long grid = (long long)XCDS * ids_per_xcd((long long)tiles_m * tiles_n) * splits;
     if (grid > 0x7fffffffLL) return note_hip_error("down_mfma grid", hipErrorInvalidValue);
     ProfileScope ps(MLPMOE_KERNEL_DOWN_MFMA, a.stream);
-    down_mfma<BMT, WM, NB, kRouted><<<(unsigned)grid, WM * 128, 0, a.stream>>>(
+    down_mfma<BMT, WM, NB, D, kRouted><<<(unsigned)grid, WM * 128, 0, a.stream>>>(
         static_cast<const uint16_t *>(a.H), static_cast<const uint16_t *>(a.Wd),
         splits > 1 ? a.partial : a.out, a.T, a.d_model, a.d_inter, a.ldh, tiles_m, tiles_n, splits, kt_total,
         (a.out_bf16 && splits == 1) ? DST_BF16 : DST_F32, a.route_scratch, bt);
@@ -1038,9 +1050,11 @@ template <bool kRouted>
 static hipError_t down_and_reduce(const FwdArgs &a, const BranchTable &bt, const DownPlan &pl)
 {
     hipError_t e;
-    if (pl.shape == TILE_WIDE) e = launch_down<BM, MFMA_WM, 4, kRouted>(a, bt, pl.splits);
-    else if (pl.shape == TILE_NARROW) e = launch_down<BM, MFMA_WM, 2, kRouted>(a, bt, pl.splits);
-    else e = kRouted ? hipErrorInvalidValue : launch_down<BM_SMALL, SMALL_WM, 2, false>(a, bt, pl.splits);
+    if (pl.shape == TILE_WIDE) e = launch_down<BM, MFMA_WM, 4, 2, kRouted>(a, bt, pl.splits);
+    else if (pl.shape == TILE_NARROW) e = launch_down<BM, MFMA_WM, 2, 2, kRouted>(a, bt, pl.splits);
+    else if (kRouted) e = hipErrorInvalidValue;
+    else if (pl.shape == TILE_SMALL) e = launch_down<BM_SMALL, SMALL_WM, 2, 2, false>(a, bt, pl.splits);
+    else e = launch_down<BM_SMALL, SMALL_WM, 2, DEEP_D, false>(a, bt, pl.splits);
     if (e != hipSuccess) return hipErrorLaunchFailure;
     if (pl.splits > 1) {
         ProfileScope ps(MLPMOE_KERNEL_SPLITK_REDUCE, a.stream);
@@ -1056,7 +1070,7 @@ static hipError_t down_and_reduce(const FwdArgs &a, const BranchTable &bt, const
 // device).  a.route_scratch is route_scratch_bytes(T, d_inter) bytes, 256-byte aligned.
 hipError_t launch_mfma_routed_bf16(const FwdArgs &a, const BranchTable &bt)
 {
-    hipError_t e = launch_gate_up<BM, MFMA_WM, 4, true>(a, bt);
+    hipError_t e = launch_gate_up<BM, MFMA_WM, 4, 2, true>(a, bt);
     if (e != hipSuccess) return hipErrorLaunchFailure;
     // 256-token tiles (the routing tables are per 256 tokens); narrow when K is split: half the partial sums
     int splits = down_splits(a.T, a.d_model, bt.d_eff, TILE_WIDE);
@@ -1074,6 +1088,7 @@ hipError_t launch_mfma_bf16(const FwdArgs &a, const BranchTable &bt)
     hipError_t e = gu == TILE_WIDE     ? launch_gate_up<BM, MFMA_WM, 4>(a, bt)
                    : gu == TILE_NARROW ? launch_gate_up<BM, MFMA_WM, 2>(a, bt)
                    : gu == TILE_SMALL  ? launch_gate_up<BM_SMALL, SMALL_WM, 2>(a, bt)
+                   : gu == TILE_DEEP   ? launch_gate_up<BM_SMALL, SMALL_WM, 2, DEEP_D>(a, bt)
                                        : launch_gate_up_mixed(a, bt);
     if (e != hipSuccess) return hipErrorLaunchFailure;
     return down_and_reduce<false>(a, bt, pl);

@@ -133,7 +133,7 @@ int forward_table(const BranchTable &bt, bool aligned, const void *x, const void
     if (path == MLPMOE_PATH_AUTO)
         path = !aligned ? MLPMOE_PATH_GENERIC : (T <= 16 ? MLPMOE_PATH_DECODE : MLPMOE_PATH_MFMA);
     int tile_shape = -1;
-    if (path >= MLPMOE_PATH_MFMA_WIDE && path <= MLPMOE_PATH_MFMA_MIXED) {
+    if (path >= MLPMOE_PATH_MFMA_WIDE && path <= MLPMOE_PATH_MFMA_DEEP) {
         tile_shape = path - MLPMOE_PATH_MFMA_WIDE;
         path = MLPMOE_PATH_MFMA;
         if (route && tile_shape >= 2) return MLPMOE_ERR_UNSUPPORTED;     // routed: 256-token tiles of one width
@@ -182,7 +182,7 @@ int forward_impl(const void *x, const void *Wg, const void *Wu, const void *Wd, 
 {
     int rc = validate_common(x, Wg, Wu, Wd, off, alpha, mask, T, d_model, d_inter, B, out);
     if (rc != MLPMOE_OK) return rc;
-    if (path < MLPMOE_PATH_AUTO || path > MLPMOE_PATH_MFMA_MIXED) return MLPMOE_ERR_UNSUPPORTED;
+    if (path < MLPMOE_PATH_AUTO || path > MLPMOE_PATH_MFMA_DEEP) return MLPMOE_ERR_UNSUPPORTED;
     if (T == 0) return MLPMOE_OK;
     BranchTable bt;
     build_table(off, alpha, mask, B, bt);

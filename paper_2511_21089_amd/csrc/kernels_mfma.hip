@@ -1,16 +1,19 @@
 // Prefill path: bf16 MFMA kernels for gfx950 (v_mfma_f32_16x16x32_bf16, wave64).
 //
 // Kernel 1  gate_up_mfma:  H[t,j] = bf16( alpha_b(j) * SiLU(<x_t,Wg_j>) * <x_t,Wu_j> )
-//           one 256-token x 128-neuron tile per workgroup with TWO fp32 accumulator sets
-//           (gate and up), so the gated product of Sec. 3.1's inner bracket is formed in
-//           registers and only H (bf16) leaves the CU.
+//           one tile of tokens x neurons per workgroup with TWO fp32 accumulator sets (gate and
+//           up), so the gated product of Sec. 3.1's inner bracket is formed in registers and
+//           only H (bf16) leaves the CU.
 // Kernel 2  down_mfma:     out[t,m] = sum_{j in active runs} H[t,j] * Wd[m,j]
-//           one 256x256 tile per workgroup; the K loop walks every active run back to back,
-//           so the sum over branches of Sec. 3.1 is one fp32 accumulation with no per-branch
-//           round trip.  Small outputs are split along K into deterministic partial sums.
+//           one tile of tokens x output features per workgroup; the K loop walks every active
+//           run back to back, so the sum over branches of Sec. 3.1 is one fp32 accumulation with
+//           no per-branch round trip.  Small outputs are split along K into partial sums that a
+//           second kernel adds up in a fixed order.
 //
-// Both kernels share one main loop: 256 A rows (tokens) against two blocks of 128 B rows, waves in
-// a WM x 2 arrangement, each wave owning (256 / WM) x (64+64) outputs as 16x16 MFMA tiles.  The
+// Both kernels share one main loop: BMT A rows (tokens) against two blocks of 32 NB B rows, waves in
+// a WM x 2 arrangement, each wave owning (BMT / WM) x (16 NB + 16 NB) outputs as 16x16 MFMA tiles.
+// Tile shapes in use: 256 x (128 + 128) and 256 x (64 + 64) with 8 waves and the whole LDS of a CU,
+// 128 x (64 + 64) with 4 waves and either half the LDS (two workgroups per CU) or a deeper ring.  The
 // 16x16x32 shape is used rather than 32x32x16 because the chip is power limited on this work: with
 // random operands a pure stream of 16x16x32 MFMAs sustains 2.0 PFLOP/s, one of 32x32x16 1.7.
 #include <algorithm>
@@ -136,27 +139,26 @@ __device__ __forceinline__ KCursor k_seek(const KR &kr, int tile)
     return c;
 }
 
-// LDS layout.  The LDS is a ring of five 32 KiB parts.  A part holds 256 rows of 128 bytes
-// (8 chunks of 8 bf16): either the A rows (tokens) of one K tile, or its B rows (128 rows of
-// the first B block, then 128 of the second).  Parts are filled in the order A0 B0 A1 B1 A2 B2 ...,
-// part number s going to ring slot s % 5, so while K tile i is being used the parts of tile i+1
-// and the A part of tile i+2 are landing.  Chunk c of row r is stored at chunk slot c ^ swz(r),
+// LDS layout.  The LDS is a ring of 2 D + 1 parts (five parts of 32 KiB for the 256-token tiles).  A part
+// holds rows of 128 bytes (8 chunks of 8 bf16): either the A rows (tokens) of one K tile, or its B rows (the
+// rows of the first B block, then those of the second).  Parts are filled in the order A0 B0 A1 B1 A2 B2 ...,
+// part number s going to ring slot s % (2 D + 1), so while K tile i is being used the parts of tiles i+1 ..
+// i+D-1 and the A part of tile i+D are landing.  Chunk c of row r is stored at chunk slot c ^ swz(r),
 // swz(r) = (r & 7) ^ ((r >> 3) & 1), so that the 16-byte reads of 32 consecutive rows at one
 // logical chunk (and of 16 consecutive rows at 4 consecutive chunks) fall on distinct banks.  A direct-to-LDS wave load writes 1 KiB = 8 whole rows,
 // and each row is one full 128-byte line of global memory (half lines cost the same L2 -> CU
 // transfer as whole ones); the swizzle is applied on the global side: the lane that fills slot p
 // of row r fetches logical chunk p ^ swz(r).
 //
-// Main loop, WM x 2 waves (WM = 2: 4 waves of 128 x (64+64) outputs; WM = 4: 8 waves of
-// 64 x (64+64)).  A_tile / B0_tile / B1_tile point at the first row of the tile (wave uniform);
+// Main loop, WM x 2 waves.  A_tile / B0_tile / B1_tile point at the first row of the tile (wave uniform);
 // a_valid / b0_valid / b1_valid are the rows that exist from there on (>= 1).  Rows past that
 // are clamped to the last valid row: their results are never stored and MFMA rows / columns do
 // not mix.  K chunks past the end of a range are read from a zero chunk, in A and in B.
 // Schedule of K tile i (two K steps of 32; fragments are double buffered one step ahead):
-//   step 0: MFMAs; read step 1's fragments; issue the A part of tile i+2
-//   barrier: parts of tile i+1 have landed (only the newest A part may be in flight) and every
-//            wave has read its last fragments of tile i, whose two ring slots are free again
-//   step 1: MFMAs; read step 0's fragments of tile i+1; issue the B part of tile i+2
+//   step 0: MFMAs; read step 1's fragments; issue the A part of tile i+D
+//   barrier: parts of tile i+1 have landed (only the loads issued after them may be in flight) and
+//            every wave has read its last fragments of tile i, whose two ring slots are free again
+//   step 1: MFMAs; read step 0's fragments of tile i+1; issue the B part of tile i+D
 // The direct loads are spread over the steps (one per wave every other MFMA slot) because a
 // CU's vector memory path takes about as long to move a tile as the MFMAs take to consume it:
 // issued in bursts, the loads back up in the issue queue and the MFMAs behind them wait.

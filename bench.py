@@ -34,12 +34,7 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 # --copy-mib.  Valid only for the kernel source it was measured on: keyed by that file's SHA-256,
 # and reported as null when the source has changed since.
 TRAFFIC = {
-    # (workload, kernel): (sha256 of the kernel's source file, bytes per launch = read + written)
-    # gate_up_mfma at T=4096: 1409.4 MB read (x is re-read once per group of 4 neuron tiles and the
-    # weights once per XCD that needs them: 5.3x the 268 MB the kernel has to read) + 117.5 MB written
-    ("llama8b_T4096", "gate_up_mfma"): ("3ef1f5a0fb5405e74cacc34332055048e5b29b071a3425de39efeaaa99ae4129", 1526.9e6),
-    # decode gate+up at T=1: 235.1 MB read (the weights, once) + 0.1 MB written
-    ("llama8b_T1", "decode_gate_up"): ("18d415ba7d819bbcc6fbeeb8894c0ae35e6839accc6af4dd939c644dd423245c", 235.2e6),
+    # (workload, kernel): (sha256 of the kernel's source file, bytes per launch = read + written, summary file)
 }
 PREWARM_S = 0.1          # untimed repetitions of the step before the warm-up steps (see time_steps)
 KERNEL_SOURCE = {"gate_up_mfma": "kernels_mfma.hip", "down_mfma": "kernels_mfma.hip",
@@ -47,15 +42,18 @@ KERNEL_SOURCE = {"gate_up_mfma": "kernels_mfma.hip", "down_mfma": "kernels_mfma.
 
 
 def traffic_of(workload, kernel):
+    """(bytes per launch, where the figure comes from), or (None, None) when there is none for the kernel source
+    as it stands: the counters are not read by this run, they were taken by the rocprofv3 runs whose summary the
+    second element names."""
     ent = TRAFFIC.get((workload, kernel))
     src = KERNEL_SOURCE.get(kernel)
     if ent is None or src is None:
-        return None
+        return None, None
     path = os.path.join(ROOT, "paper_2511_21089_amd", "csrc", src)
     with open(path, "rb") as f:
         if hashlib.sha256(f.read()).hexdigest() != ent[0]:
-            return None
-    return ent[1]
+            return None, None
+    return ent[1], ent[2]
 
 
 def parse():
@@ -157,13 +155,15 @@ def roofline_of(per_kernel, T, d_model, d_eff, decode, workload=None):
         wbytes = (2 if gate_up else 1) * d_model * d_eff * 2
         io = T * d_model * 2 + T * d_eff * 2 if gate_up else T * d_eff * 2 + T * d_model * 4
         ach = (wbytes + io) / (avg_ms * 1e-3) / 1e9
+        traffic, source = traffic_of(workload, dom)
         return {"kernel": dom, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": traffic_of(workload, dom),
+                "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": traffic, "traffic_source": source,
                 "avg_kernel_us": round(avg_ms * 1e3, 2)}
     flops = (4.0 if gate_up else 2.0) * T * d_model * d_eff
     ach = flops / (avg_ms * 1e-3) / 1e12
+    traffic, source = traffic_of(workload, dom)
     return {"kernel": dom, "bound": "mfma", "achieved": round(ach, 1), "peak": MFMA_PEAK_TFLOPS,
-            "unit": "TFLOP/s", "frac": round(ach / MFMA_PEAK_TFLOPS, 4), "traffic": traffic_of(workload, dom),
+            "unit": "TFLOP/s", "frac": round(ach / MFMA_PEAK_TFLOPS, 4), "traffic": traffic, "traffic_source": source,
             "avg_kernel_us": round(avg_ms * 1e3, 2)}
 
 
@@ -191,7 +191,7 @@ def others(mm, synth, torch, seed):
     """Short runs of the remaining workloads: tokens/s and the fraction of the roofline that bounds them."""
     res = {}
     for name, Ts in (("qwen05b", (2048, 1)), ("qwen05b_pruned", (2048, 16, 1)), ("llama8b_fade", (4096, 16, 1)),
-                     ("llama8b", (512, 256, 64))):
+                     ("llama8b", (512, 256, 128, 64))):
         Tmax = max(Ts)
         L, x, dev, _, off, alpha, mask, d_eff = build_layer(mm, synth, name, Tmax, seed)
         w = L.workload

@@ -73,7 +73,8 @@ enum {
     MLPMOE_PATH_MFMA_SMALL = 6,  /* 128 tokens x (64 + 64) / 128, 4 waves, two workgroups per CU       */
     MLPMOE_PATH_MFMA_MIXED = 7,  /* gate+up: WIDE for the full rounds of 256 workgroups, NARROW for a
                                     remainder of at most half a round (WIDE if there is none); down: chosen */
-    MLPMOE_PATH_MFMA_DEEP = 8    /* SMALL's tile with four K tiles requested ahead, one workgroup per CU */
+    MLPMOE_PATH_MFMA_DEEP = 8,   /* SMALL's tile with four K tiles requested ahead, one workgroup per CU */
+    MLPMOE_PATH_MFMA_SLIM = 9    /* 64 tokens x (64 + 64) / 128, 4 waves, five K tiles requested ahead   */
 };
 
 /* Human-readable name of a status code (static string, never NULL). */

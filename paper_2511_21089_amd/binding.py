@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_PKG, "libmlpmoe.so")
 OK = 0
 ERR_NULL, ERR_SHAPE, ERR_OFFSETS, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, ERR_ALIGN = -1, -2, -3, -4, -5, -6, -7
 PATH_AUTO, PATH_GENERIC, PATH_MFMA, PATH_DECODE = 0, 1, 2, 3
-PATH_MFMA_WIDE, PATH_MFMA_NARROW, PATH_MFMA_SMALL, PATH_MFMA_MIXED, PATH_MFMA_DEEP = 4, 5, 6, 7, 8
+PATH_MFMA_WIDE, PATH_MFMA_NARROW, PATH_MFMA_SMALL, PATH_MFMA_MIXED, PATH_MFMA_DEEP, PATH_MFMA_SLIM = 4, 5, 6, 7, 8, 9
 MAX_BRANCHES = 64
 
 EXPORTS = ["mlpmoe_status_string", "mlpmoe_last_error_detail", "mlpmoe_slice", "mlpmoe_compact", "mlpmoe_fade", "mlpmoe_fade_neurons", "mlpmoe_workspace_bytes",

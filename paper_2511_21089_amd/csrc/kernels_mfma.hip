@@ -33,16 +33,25 @@ constexpr int BM = 256;          // tokens per tile of the large-tile kernels (a
 constexpr int BM_SMALL = 128;    // tokens per tile of the small-tile kernels
 constexpr int BNH_MAX = 128;     // rows of each of the two B blocks: 32 * NB, NB = 4 (128) or 2 (64)
 constexpr int BK = 64;           // K elements per tile: one tile row is 128 bytes = one cache line
-// The LDS is a ring of 2 D + 1 parts, D = K tiles requested ahead of the one in use (A0 B0 A1 B1 A2 | B2 A3 ...
-// for D = 2, the depth of the 256-token tiles, whose ring then fills the LDS of a CU).
+// The LDS is a ring that keeps the K tile in use and the D tiles requested ahead of it.  Two layouts:
+//   alternating (the 256-token tiles): 2 D + 1 parts of equal size, A0 B0 A1 B1 A2 | B2 A3 ...; with D = 2 the
+//       ring fills the LDS of a CU (five parts of 32 KiB), half a K tile less than whole stages would need;
+//   staged: D + 1 stages, a stage being the A rows followed by the B rows of one K tile.  Nothing is padded, so
+//       tiles with fewer A rows than B rows keep more K tiles in flight in the same LDS.
 __host__ __device__ constexpr int n_parts(int depth) { return 2 * depth + 1; }
-// A part of the ring holds the A rows (BMT tokens), or the B rows (2 blocks of 32 NB), of one K tile.
+// A part of the alternating ring holds the A rows (BMT tokens), or the B rows (2 blocks of 32 NB), of one K tile.
 // 256-token tiles: 32 KiB parts, the ring is the whole LDS of a CU (one workgroup of 8 waves per CU).
 // 128-token tiles with NB = 2: 16 KiB parts, 80 KiB per workgroup of 4 waves, two workgroups per CU.
 __host__ __device__ constexpr int part_bytes(int bmt, int nb) { return (bmt > 64 * nb ? bmt : 64 * nb) * BK * 2; }
-__host__ __device__ constexpr int lds_bytes(int bmt, int nb, int depth = 2) { return n_parts(depth) * part_bytes(bmt, nb); }
+__host__ __device__ constexpr int stage_bytes(int bmt, int nb) { return (bmt + 64 * nb) * BK * 2; }
+__host__ __device__ constexpr int lds_bytes(int bmt, int nb, int depth = 2, bool staged = false)
+{
+    return staged ? (depth + 1) * stage_bytes(bmt, nb) : n_parts(depth) * part_bytes(bmt, nb);
+}
 constexpr int MFMA_WM = 4;                           // waves along M of the 256-token tiles: 8 waves of 64 x (64+64) outputs
 constexpr int SMALL_WM = 2;                          // ... of the 128-token tiles: 4 waves of 64 x (32+32)
+constexpr int BM_SLIM = 64;                          // tokens per tile of the slim kernels: 4 waves of 32 x (32+32)
+constexpr int SLIM_WM = 2;
 
 enum { DST_F32 = 0, DST_BF16 = 1 };     // how down_mfma writes its result
 
@@ -165,7 +174,7 @@ __device__ __forceinline__ KCursor k_seek(const KR &kr, int tile)
 // NB = 16-row MFMA pieces per B block per wave: 4 (B blocks of 128 rows, a 256 x 256 tile) or 2 (B
 // blocks of 64 rows, a 256 x 128 tile, for shapes that would otherwise leave most CUs without a
 // tile in the last round).  A B part of 64 + 64 rows fills half of its ring slot.
-template <int BMT, int WM, int NB, int D, bool kRowsAreB, typename KR>
+template <int BMT, int WM, int NB, int D, bool kStaged, bool kRowsAreB, typename KR>
 __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, int lda, int a_valid,
                                          const uint16_t *__restrict__ B0_tile,
                                          const uint16_t *__restrict__ B1_tile, int ldb, int b0_valid,
@@ -179,12 +188,19 @@ __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, in
     constexpr int PLB = 8 * NB / NWAVES;          // ... per B part
     constexpr int N_SLOTS = MI * NB / 2;          // slots of 4 MFMAs per K step
     constexpr int N_PIECES = 2 * NB + MI;         // fragment pieces per K step
-    constexpr int PART_BYTES = part_bytes(BMT, NB);
-    constexpr int N_PARTS = n_parts(D);
+    constexpr int RPS = (N_PIECES + N_SLOTS - 1) / N_SLOTS < 2 ? 2 : (N_PIECES + N_SLOTS - 1) / N_SLOTS;   // fragment reads per slot
+    // Ring geometry in bytes: where the A part of the first K tile and its B part sit, how far the next tile's
+    // parts are from this tile's, and where the ring wraps.
+    // direct loads of a part, spread over the slots of a K step: every *_EVERY-th slot issues *_PER of them
+    constexpr int A_EVERY = PL <= N_SLOTS ? N_SLOTS / PL : 1, A_PER = PL <= N_SLOTS ? 1 : PL / N_SLOTS;
+    constexpr int B_EVERY = PLB <= N_SLOTS ? N_SLOTS / PLB : 1, B_PER = PLB <= N_SLOTS ? 1 : PLB / N_SLOTS;
+    constexpr int B_FIRST = kStaged ? BMT * 128 : part_bytes(BMT, NB);
+    constexpr int RING_STEP = kStaged ? stage_bytes(BMT, NB) : 2 * part_bytes(BMT, NB);
+    constexpr int RING_BYTES = lds_bytes(BMT, NB, D, kStaged);
     static_assert(D >= 2, "one tile in use, at least one more on its way");
-    static_assert(N_SLOTS % PL == 0 && N_SLOTS % PLB == 0 && PL % 2 == 0 && PLB % 2 == 0,
+    static_assert((N_SLOTS % PL == 0 || PL % N_SLOTS == 0) && (N_SLOTS % PLB == 0 || PLB % N_SLOTS == 0) &&
+                      PL % 2 == 0 && PLB % 2 == 0,
                   "loads spread evenly over the slots, slab parity is load parity");
-    static_assert(2 * N_SLOTS >= N_PIECES, "two fragment reads per slot cover a K step");
     const int nk = kt_end - kt_begin;
     if (nk <= 0) return;
     const int tid = threadIdx.x;
@@ -225,7 +241,7 @@ __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, in
     // left, reads the zero chunk instead.  Branch free, so that the loads sit in the same basic
     // block as the MFMAs and every part is always the same number of loads.
     struct Issue {
-        int run, k, kend, left, slot;
+        int run, k, kend, left, off;              // off: byte offset in the ring of the part to be filled next
     };
     auto advance = [&](Issue &q) {                // stays on the last range once the list is exhausted
         q.k += BK;
@@ -235,8 +251,8 @@ __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, in
             q.kend = kr.end(q.run);
         }
         --q.left;
-        q.slot += 2;
-        if (q.slot >= N_PARTS) q.slot -= N_PARTS;
+        q.off += RING_STEP;
+        if (q.off >= RING_BYTES) q.off -= RING_BYTES;
     };
     // what the loads of one part have in common
     struct Part {
@@ -248,7 +264,7 @@ __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, in
         Part pt;
         const int kend = q.left > 0 ? q.kend : -(1 << 30);
         pt.src = base + (size_t)q.k * 2;
-        pt.dst = w_dst + q.slot * PART_BYTES;
+        pt.dst = w_dst + q.off;
         pt.ok[0] = q.k + cl0 * 8 < kend;
         pt.ok[1] = q.k + (cl0 ^ 1) * 8 < kend;
         return pt;
@@ -280,14 +296,14 @@ __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, in
     struct Frags {
         bf16x8 v[N_PIECES];
     };
-    auto read_piece = [&](Frags &f, int g, int a_slot, int ks) {
-        // the B part of a tile sits in the ring slot after its A part
-        const int b_slot = a_slot + 1 < N_PARTS ? a_slot + 1 : 0;
+    auto read_piece = [&](Frags &f, int g, int a_at, int ks) {
+        // the B part of a tile follows its A part (alternating ring: in the next part, which may be the first)
+        const int b_at = kStaged ? a_at + B_FIRST : (a_at + B_FIRST < RING_BYTES ? a_at + B_FIRST : 0);
         if (g < 2 * NB)
-            f.v[g] = *reinterpret_cast<const bf16x8 *>(lds + b_slot * PART_BYTES + b_rd[ks] + (g / NB) * (BNH * 128) +
+            f.v[g] = *reinterpret_cast<const bf16x8 *>(lds + b_at + b_rd[ks] + (g / NB) * (BNH * 128) +
                                                        (g % NB) * (16 * 128));
         else
-            f.v[g] = *reinterpret_cast<const bf16x8 *>(lds + a_slot * PART_BYTES + a_rd[ks] + (g - 2 * NB) * (16 * 128));
+            f.v[g] = *reinterpret_cast<const bf16x8 *>(lds + a_at + a_rd[ks] + (g - 2 * NB) * (16 * 128));
     };
     // kRowsAreB: the B rows (weights) are the MFMA's row operand and the A rows (tokens) its column
     // operand.  In the 16x16 result lane l then holds column l & 15 = one token and rows
@@ -305,7 +321,7 @@ __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, in
     // first MFMA of a step (direct-to-LDS loads in flight make it give up exact counting), so the
     // reads are packed into the early slots and the last slots leave them time to land.
     // DMA: 1 loads of the A part pt, 2 loads of the B part pt.
-    auto k_step = [&](const Frags &cur_f, Frags &nxt_f, int rd_slot, int rd_ks, int dma, const Part &pt) {
+    auto k_step = [&](const Frags &cur_f, Frags &nxt_f, int rd_at, int rd_ks, int dma, const Part &pt) {
 #pragma unroll
         for (int g = 0; g < N_SLOTS; ++g) {
             // The two waves of a SIMD take the matrix pipe in turns of four MFMAs.  A wave asks
@@ -319,10 +335,17 @@ __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, in
             for (int q = 1; q < 4; ++q) mfma_n(cur_f, 4 * g + q);
             __builtin_amdgcn_s_setprio(0);
             __builtin_amdgcn_sched_barrier(0);
-            if (2 * g < N_PIECES) read_piece(nxt_f, 2 * g, rd_slot, rd_ks);
-            if (2 * g + 1 < N_PIECES) read_piece(nxt_f, 2 * g + 1, rd_slot, rd_ks);
-            if (dma == 1 && g % (N_SLOTS / PL) == 0) dma_part(g / (N_SLOTS / PL), pt, a_off);
-            if (dma == 2 && g % (N_SLOTS / PLB) == 0) dma_part(g / (N_SLOTS / PLB), pt, b_off);
+#pragma unroll
+            for (int r = 0; r < RPS; ++r)
+                if (RPS * g + r < N_PIECES) read_piece(nxt_f, RPS * g + r, rd_at, rd_ks);
+            if (dma == 1 && g % A_EVERY == 0) {
+#pragma unroll
+                for (int l = 0; l < A_PER; ++l) dma_part((g / A_EVERY) * A_PER + l, pt, a_off);
+            }
+            if (dma == 2 && g % B_EVERY == 0) {
+#pragma unroll
+                for (int l = 0; l < B_PER; ++l) dma_part((g / B_EVERY) * B_PER + l, pt, b_off);
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -335,9 +358,9 @@ __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, in
         qa.k = c.k;
         qa.kend = kr.end(c.run);
         qa.left = nk;
-        qa.slot = 0;
+        qa.off = 0;
         qb = qa;
-        qb.slot = 1;
+        qb.off = B_FIRST;
     }
 #pragma unroll
     for (int p = 0; p < D; ++p) {
@@ -354,14 +377,14 @@ __device__ __forceinline__ void mainloop(const uint16_t *__restrict__ A_tile, in
 #pragma unroll
     for (int g = 0; g < N_PIECES; ++g) read_piece(f0, g, 0, 0);
 
-    int rd = 0;                                   // ring slot of the A part of the tile in use
+    int rd = 0;                                   // byte offset in the ring of the A part of the tile in use
     for (int it = 0; it < nk; ++it) {
         const Part pa = part_of(qa, a_base, wa_dst);
         k_step(f0, f1, rd, 1, 1, pa);             // + A part of tile it+D
         advance(qa);
         // tile it+1 has landed (the newer tiles and the A part just issued may be in flight); tile it's slots are free
         pipeline_barrier<(D - 2) * (PL + PLB) + PL>();
-        rd = rd + 2 < N_PARTS ? rd + 2 : rd + 2 - N_PARTS;
+        rd = rd + RING_STEP < RING_BYTES ? rd + RING_STEP : rd + RING_STEP - RING_BYTES;
         const Part pb = part_of(qb, b_base, wb_dst);
         k_step(f1, f0, rd, 0, 2, pb);             // + B part of tile it+D
         advance(qb);
@@ -452,7 +475,7 @@ __device__ __forceinline__ bool neuron_tile(const BranchTable &bt, int tn, int b
 
 // One tile of the gate+up projection: tokens tm * BMT .., neurons n0 .. min(n0 + 32 NB, n_end) of a run that
 // ends at n_end.  lds: lds_bytes(BMT, NB, D) bytes.
-template <int BMT, int WM, int NB, int D, bool kRouted>
+template <int BMT, int WM, int NB, int D, bool kStaged, bool kRouted>
 __device__ __forceinline__ void gate_up_tile(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
                                              const uint16_t *__restrict__ Wu, uint16_t *__restrict__ H, int T,
                                              int d_model, int ldh, const uint8_t *__restrict__ route,
@@ -472,7 +495,7 @@ __device__ __forceinline__ void gate_up_tile(const uint16_t *__restrict__ X, con
         }
 
     const int nk = (d_model + BK - 1) / BK;
-    mainloop<BMT, WM, NB, D, true>(X + (size_t)t0 * d_model, d_model, T - t0, Wg + (size_t)n0 * d_model,
+    mainloop<BMT, WM, NB, D, kStaged, true>(X + (size_t)t0 * d_model, d_model, T - t0, Wg + (size_t)n0 * d_model,
                        Wu + (size_t)n0 * d_model, d_model, n_end - n0, n_end - n0, KSingle{d_model}, 0, nk,
                        lds, accg, accu);
 
@@ -521,7 +544,7 @@ __device__ __forceinline__ void gate_up_tile(const uint16_t *__restrict__ X, con
 // over the full grid (one contiguous stretch of the list per XCD), the ids left over exit.  The
 // down projection skips the same (token tile, branch) pairs, and H is multiplied by the token's
 // route bit, so that it is exactly 0 where a token does not take a branch.
-template <int BMT, int WM, int NB, int D, bool kRouted>
+template <int BMT, int WM, int NB, int D, bool kStaged, bool kRouted>
 __global__ void __launch_bounds__(WM * 128)
 gate_up_mfma(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
              const uint16_t *__restrict__ Wu, uint16_t *__restrict__ H, int T, int d_model, int d_inter,
@@ -529,7 +552,7 @@ gate_up_mfma(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
              BranchTable bt)
 {
     static_assert(!kRouted || BMT == BM, "the routed path's tables are per 256 tokens");
-    __shared__ __attribute__((aligned(1024))) char lds[lds_bytes(BMT, NB, D)];
+    __shared__ __attribute__((aligned(1024))) char lds[lds_bytes(BMT, NB, D, kStaged)];
     constexpr int BNH = 32 * NB;                  // neurons per tile
     int tm, tn;
     if (kRouted) {
@@ -556,7 +579,7 @@ gate_up_mfma(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
     }
     int n0, n_end;
     if (!neuron_tile(bt, tn, BNH, n0, n_end)) return;
-    gate_up_tile<BMT, WM, NB, D, kRouted>(X, Wg, Wu, H, T, d_model, ldh, route, bt, lds, tm, n0, n_end);
+    gate_up_tile<BMT, WM, NB, D, kStaged, kRouted>(X, Wg, Wu, H, T, d_model, ldh, route, bt, lds, tm, n0, n_end);
 }
 
 // The gate+up projection with WIDE tiles for the full rounds of 256 workgroups and NARROW tiles for what
@@ -584,7 +607,7 @@ gate_up_mfma_mixed(const uint16_t *__restrict__ X, const uint16_t *__restrict__ 
         if (logical >= xcd_end) return;
         tile_from_logical(logical, tiles_m, tiles_n, tm, tn);
         if (!neuron_tile(bt, tn, 128, n0, n_end)) return;
-        gate_up_tile<BM, WM, 4, 2, false>(X, Wg, Wu, H, T, d_model, ldh, nullptr, bt, lds, tm, n0, n_end);
+        gate_up_tile<BM, WM, 4, 2, false, false>(X, Wg, Wu, H, T, d_model, ldh, nullptr, bt, lds, tm, n0, n_end);
     } else {
         k -= wide_per_xcd;
         const int logical = xcd * P + wide_per_xcd + k / 2;
@@ -593,7 +616,7 @@ gate_up_mfma_mixed(const uint16_t *__restrict__ X, const uint16_t *__restrict__ 
         if (!neuron_tile(bt, tn, 128, n0, n_end)) return;
         n0 += (k % 2) * 64;
         if (n0 >= n_end) return;                                   // the run ends in the first half
-        gate_up_tile<BM, WM, 2, 2, false>(X, Wg, Wu, H, T, d_model, ldh, nullptr, bt, lds, tm, n0, n_end);
+        gate_up_tile<BM, WM, 2, 2, false, false>(X, Wg, Wu, H, T, d_model, ldh, nullptr, bt, lds, tm, n0, n_end);
     }
 }
 
@@ -602,14 +625,14 @@ gate_up_mfma_mixed(const uint16_t *__restrict__ X, const uint16_t *__restrict__ 
 // rounded once (RNE).
 // kRouted: the K loop of token tile tm walks only the branches some token of the tile is routed
 // to (tile_need); H is 0 for the tokens of the tile that do not take a branch.
-template <int BMT, int WM, int NB, int D, bool kRouted>
+template <int BMT, int WM, int NB, int D, bool kStaged, bool kRouted>
 __global__ void __launch_bounds__(WM * 128)
 down_mfma(const uint16_t *__restrict__ H, const uint16_t *__restrict__ Wd, float *__restrict__ dst, int T,
           int d_model, int d_inter, int ldh, int tiles_m, int tiles_n, int splits, int kt_total, int dst_mode,
           const uint8_t *__restrict__ tile_need, BranchTable bt)
 {
     static_assert(!kRouted || BMT == BM, "the routed path's tables are per 256 tokens");
-    __shared__ __attribute__((aligned(1024))) char lds[lds_bytes(BMT, NB, D)];
+    __shared__ __attribute__((aligned(1024))) char lds[lds_bytes(BMT, NB, D, kStaged)];
     const int per_split = XCDS * ids_per_xcd((long long)tiles_m * tiles_n);
     const int z = blockIdx.x / per_split;
     int tm, tn;
@@ -638,11 +661,11 @@ down_mfma(const uint16_t *__restrict__ H, const uint16_t *__restrict__ Wd, float
     // the second block of output features may start past d_model: point it at the last row
     const int n1 = n0 + BNH < d_model ? n0 + BNH : d_model - 1;
     if (kRouted)
-        mainloop<BMT, WM, NB, D, true>(H + (size_t)t0 * ldh, ldh, T - t0, Wd + (size_t)n0 * d_inter,
+        mainloop<BMT, WM, NB, D, kStaged, true>(H + (size_t)t0 * ldh, ldh, T - t0, Wd + (size_t)n0 * d_inter,
                                     Wd + (size_t)n1 * d_inter, d_inter, d_model - n0, d_model - n1, dyn, kt_begin,
                                     kt_end, lds, acc0, acc1);
     else
-        mainloop<BMT, WM, NB, D, true>(H + (size_t)t0 * ldh, ldh, T - t0, Wd + (size_t)n0 * d_inter,
+        mainloop<BMT, WM, NB, D, kStaged, true>(H + (size_t)t0 * ldh, ldh, T - t0, Wd + (size_t)n0 * d_inter,
                                     Wd + (size_t)n1 * d_inter, d_inter, d_model - n0, d_model - n1, KRuns{bt},
                                     kt_begin, kt_end, lds, acc0, acc1);
 
@@ -838,13 +861,31 @@ int k_tiles(const BranchTable &bt)
 // DEEP: SMALL's tile with four K tiles requested ahead instead of two (a ring of 9 parts, 144 KiB, one
 // workgroup per CU): for batches of a few dozen to a hundred tokens, where a launch has about one tile per
 // CU and is bound by how many bytes of weights it keeps in flight, not by the matrix cores.
-enum TileShape { TILE_WIDE = 0, TILE_NARROW = 1, TILE_SMALL = 2, TILE_MIXED = 3, TILE_DEEP = 4 };
-constexpr int DEEP_D = 4;
+// SLIM: 64 tokens x (64 + 64) with 4 waves and a staged ring of five K tiles requested ahead (144 KiB, one
+// workgroup per CU): the A rows of a K tile take a third of a stage, so more bytes of the B operand are in
+// flight per CU than with any other shape; for outputs with few token rows per output feature (a down
+// projection with a short d_model can then do without a K split) and for batches of at most 64 tokens.
+enum TileShape { TILE_WIDE = 0, TILE_NARROW = 1, TILE_SMALL = 2, TILE_MIXED = 3, TILE_DEEP = 4, TILE_SLIM = 5 };
+constexpr int N_TILE_SHAPES = 6;
+constexpr int DEEP_D = 4, SLIM_D = 5;
+// compile-time side of a tile shape: tokens, waves along M, 16-row MFMA pieces per B block and wave, K tiles
+// requested ahead, ring layout
+template <int BMT_, int WM_, int NB_, int D_, bool kStaged_>
+struct ShapeT {
+    static constexpr int BMT = BMT_, WM = WM_, NB = NB_, D = D_;
+    static constexpr bool kStaged = kStaged_;
+};
+using ShapeWide = ShapeT<BM, MFMA_WM, 4, 2, false>;
+using ShapeNarrow = ShapeT<BM, MFMA_WM, 2, 2, false>;
+using ShapeSmall = ShapeT<BM_SMALL, SMALL_WM, 2, 2, false>;
+using ShapeDeep = ShapeT<BM_SMALL, SMALL_WM, 2, DEEP_D, false>;
+using ShapeSlim = ShapeT<BM_SLIM, SLIM_WM, 2, SLIM_D, true>;
 struct TileDims {
     int bm, bn;       // tokens, B rows per block (a tile has two blocks)
     int per_cu;       // workgroups resident per CU
 };
-constexpr TileDims kTileDims[5] = {{BM, 128, 1}, {BM, 64, 1}, {BM_SMALL, 64, 2}, {BM, 128, 1}, {BM_SMALL, 64, 1}};
+constexpr TileDims kTileDims[N_TILE_SHAPES] = {{BM, 128, 1}, {BM, 64, 1}, {BM_SMALL, 64, 2}, {BM, 128, 1}, {BM_SMALL, 64, 1},
+                                               {BM_SLIM, 64, 1}};
 constexpr int kCUs = 256;
 
 long long gate_up_tiles(const BranchTable &bt, int T, TileShape sh)
@@ -860,12 +901,13 @@ long long gate_up_tiles(const BranchTable &bt, int T, TileShape sh)
 // 0.62 of that, a SMALL one 0.4 (two share a CU, each at a quarter of a WIDE tile's flops but bound by the
 // traffic into the LDS; an odd one at the end runs alone at about 0.3); the fixed cost of a workgroup
 // (first loads, epilogue, hand-over) is about 7.4 / 5.2 us and 1.5 us for SMALL, whose neighbour on the CU
-// computes meanwhile; DEEP (SMALL's tile alone on its CU) 0.75 and 4.4 us.  A launch that has few tiles per CU
-// cannot stream faster than about 3.5 TB/s, 5 TB/s with DEEP's longer queue of requests.
+// computes meanwhile; DEEP (SMALL's tile alone on its CU) 0.75 and 4.4 us; SLIM 0.6 and 3.5 us.  A launch that
+// has few tiles per CU cannot stream faster than about 3.5 TB/s, 5 TB/s with DEEP's and SLIM's longer queues of
+// requests.
 constexpr double kDeepStreamBytesPerUs = 5.0e6;
 double launch_cost_us(long long tiles, int nk, TileShape sh, double bytes)
 {
-    static const double per_k[5] = {1.48, 0.92, 0.59, 1.48, 0.75}, fixed[5] = {7.4, 5.2, 1.5, 7.4, 4.4};
+    static const double per_k[N_TILE_SHAPES] = {1.48, 0.92, 0.59, 1.48, 0.75, 0.6}, fixed[N_TILE_SHAPES] = {7.4, 5.2, 1.5, 7.4, 4.4, 3.5};
     const long long per_cu = (tiles + kCUs - 1) / kCUs;       // tiles the busiest CU runs, one after the other
     double c;
     if (sh == TILE_SMALL)
@@ -873,7 +915,7 @@ double launch_cost_us(long long tiles, int nk, TileShape sh, double bytes)
     else
         c = (double)per_cu * (nk * per_k[sh] + fixed[sh]);
     // DEEP keeps twice the bytes in flight
-    return std::max(c, bytes / (sh == TILE_DEEP ? kDeepStreamBytesPerUs : 3.5e6) + fixed[sh]);
+    return std::max(c, bytes / (sh == TILE_DEEP || sh == TILE_SLIM ? kDeepStreamBytesPerUs : 3.5e6) + fixed[sh]);
 }
 
 // Wide tiles that MIXED runs as wide, per XCD (32 per full round of 256), or -1 if MIXED does not apply:
@@ -892,7 +934,8 @@ TileShape pick_gate_up_tile(const BranchTable &bt, int T, int d_model)
     const long long wide = gate_up_tiles(bt, T, TILE_WIDE);
     TileShape best = TILE_WIDE;
     double best_cost = launch_cost_us(wide, nk, TILE_WIDE, bytes);
-    for (TileShape sh : {TILE_NARROW, TILE_SMALL, TILE_DEEP}) {
+    for (TileShape sh : {TILE_NARROW, TILE_SMALL, TILE_DEEP, TILE_SLIM}) {
+        if (sh == TILE_SLIM && T > BM_SLIM) continue;           // more tokens: a taller tile reuses the weights
         const double c = launch_cost_us(gate_up_tiles(bt, T, sh), nk, sh, bytes);
         if (c < best_cost * 0.97) {
             best = sh;
@@ -932,9 +975,9 @@ DownPlan plan_down(const FwdArgs &a, const BranchTable &bt, bool routed)
     const int kt = std::max(1, k_tiles(bt));
     DownPlan best{TILE_WIDE, 1};
     double best_cost = 1e30;
-    for (TileShape sh : {TILE_WIDE, TILE_NARROW, TILE_SMALL, TILE_DEEP}) {
+    for (TileShape sh : {TILE_WIDE, TILE_NARROW, TILE_SMALL, TILE_DEEP, TILE_SLIM}) {
         if (a.tile_shape >= 0 && a.tile_shape != (int)TILE_MIXED && a.tile_shape != (int)sh) continue;
-        if (routed && (sh == TILE_SMALL || sh == TILE_DEEP)) continue;
+        if (routed && kTileDims[sh].bm != BM) continue;
         const TileDims &d = kTileDims[sh];
         const long long tiles = (long long)ceil_div(a.T, d.bm) * ceil_div(a.d_model, 2 * d.bn);
         int sp = std::min(down_splits(a.T, a.d_model, bt.d_eff, sh), kt);
@@ -977,13 +1020,14 @@ size_t mfma_partial_bytes(int T, int d_model, int d_inter)
 {
     // the largest any tile shape asks for
     int s = 1;
-    for (TileShape sh : {TILE_WIDE, TILE_NARROW, TILE_SMALL, TILE_DEEP}) s = std::max(s, down_splits(T, d_model, d_inter, sh));
+    for (TileShape sh : {TILE_WIDE, TILE_NARROW, TILE_SMALL, TILE_DEEP, TILE_SLIM}) s = std::max(s, down_splits(T, d_model, d_inter, sh));
     return s > 1 ? align_up((size_t)s * T * d_model * sizeof(float), 256) : 0;
 }
 
-template <int BMT, int WM, int NB, int D = 2, bool kRouted = false>
+template <typename S, bool kRouted = false>
 static hipError_t launch_gate_up(const FwdArgs &a, const BranchTable &bt)
 {
+    constexpr int BMT = S::BMT, WM = S::WM, NB = S::NB;
     const int tiles_m = ceil_div(a.T, BMT);
     long long tiles_n = 0;
     for (int r = 0; r < bt.n_runs; ++r) tiles_n += ceil_div(bt.run_end[r] - bt.run_start[r], 32 * NB);
@@ -1008,7 +1052,7 @@ static hipError_t launch_gate_up(const FwdArgs &a, const BranchTable &bt)
         rt = RouteTiles{need, counts, list, stride};
     }
     ProfileScope ps(MLPMOE_KERNEL_GATE_UP_MFMA, a.stream);
-    gate_up_mfma<BMT, WM, NB, D, kRouted><<<(unsigned)grid, WM * 128, 0, a.stream>>>(
+    gate_up_mfma<BMT, WM, NB, S::D, S::kStaged, kRouted><<<(unsigned)grid, WM * 128, 0, a.stream>>>(
         static_cast<const uint16_t *>(a.x), static_cast<const uint16_t *>(a.Wg),
         static_cast<const uint16_t *>(a.Wu), static_cast<uint16_t *>(a.H), a.T, a.d_model, a.d_inter,
         a.ldh, tiles_m, (int)tiles_n, a.route, rt, bt);
@@ -1031,16 +1075,17 @@ static hipError_t launch_gate_up_mixed(const FwdArgs &a, const BranchTable &bt)
     return launch_status("gate_up_mfma_mixed launch");
 }
 
-template <int BMT, int WM, int NB, int D = 2, bool kRouted = false>
+template <typename S, bool kRouted = false>
 static hipError_t launch_down(const FwdArgs &a, const BranchTable &bt, int splits)
 {
+    constexpr int BMT = S::BMT, WM = S::WM, NB = S::NB;
     const int tiles_m = ceil_div(a.T, BMT);
     const int tiles_n = ceil_div(a.d_model, 64 * NB);
     const int kt_total = k_tiles(bt);
     const long long grid = (long long)XCDS * ids_per_xcd((long long)tiles_m * tiles_n) * splits;
     if (grid > 0x7fffffffLL) return note_hip_error("down_mfma grid", hipErrorInvalidValue);
     ProfileScope ps(MLPMOE_KERNEL_DOWN_MFMA, a.stream);
-    down_mfma<BMT, WM, NB, D, kRouted><<<(unsigned)grid, WM * 128, 0, a.stream>>>(
+    down_mfma<BMT, WM, NB, S::D, S::kStaged, kRouted><<<(unsigned)grid, WM * 128, 0, a.stream>>>(
         static_cast<const uint16_t *>(a.H), static_cast<const uint16_t *>(a.Wd),
         splits > 1 ? a.partial : a.out, a.T, a.d_model, a.d_inter, a.ldh, tiles_m, tiles_n, splits, kt_total,
         (a.out_bf16 && splits == 1) ? DST_BF16 : DST_F32, a.route_scratch, bt);
@@ -1052,11 +1097,12 @@ template <bool kRouted>
 static hipError_t down_and_reduce(const FwdArgs &a, const BranchTable &bt, const DownPlan &pl)
 {
     hipError_t e;
-    if (pl.shape == TILE_WIDE) e = launch_down<BM, MFMA_WM, 4, 2, kRouted>(a, bt, pl.splits);
-    else if (pl.shape == TILE_NARROW) e = launch_down<BM, MFMA_WM, 2, 2, kRouted>(a, bt, pl.splits);
+    if (pl.shape == TILE_WIDE) e = launch_down<ShapeWide, kRouted>(a, bt, pl.splits);
+    else if (pl.shape == TILE_NARROW) e = launch_down<ShapeNarrow, kRouted>(a, bt, pl.splits);
     else if (kRouted) e = hipErrorInvalidValue;
-    else if (pl.shape == TILE_SMALL) e = launch_down<BM_SMALL, SMALL_WM, 2, 2, false>(a, bt, pl.splits);
-    else e = launch_down<BM_SMALL, SMALL_WM, 2, DEEP_D, false>(a, bt, pl.splits);
+    else if (pl.shape == TILE_SMALL) e = launch_down<ShapeSmall>(a, bt, pl.splits);
+    else if (pl.shape == TILE_DEEP) e = launch_down<ShapeDeep>(a, bt, pl.splits);
+    else e = launch_down<ShapeSlim>(a, bt, pl.splits);
     if (e != hipSuccess) return hipErrorLaunchFailure;
     if (pl.splits > 1) {
         ProfileScope ps(MLPMOE_KERNEL_SPLITK_REDUCE, a.stream);
@@ -1072,7 +1118,7 @@ static hipError_t down_and_reduce(const FwdArgs &a, const BranchTable &bt, const
 // device).  a.route_scratch is route_scratch_bytes(T, d_inter) bytes, 256-byte aligned.
 hipError_t launch_mfma_routed_bf16(const FwdArgs &a, const BranchTable &bt)
 {
-    hipError_t e = launch_gate_up<BM, MFMA_WM, 4, 2, true>(a, bt);
+    hipError_t e = launch_gate_up<ShapeWide, true>(a, bt);
     if (e != hipSuccess) return hipErrorLaunchFailure;
     // 256-token tiles (the routing tables are per 256 tokens); narrow when K is split: half the partial sums
     int splits = down_splits(a.T, a.d_model, bt.d_eff, TILE_WIDE);
@@ -1087,10 +1133,11 @@ hipError_t launch_mfma_bf16(const FwdArgs &a, const BranchTable &bt)
     const DownPlan pl = plan_down(a, bt, false);
     TileShape gu = a.tile_shape >= 0 ? (TileShape)a.tile_shape : pick_gate_up_tile(bt, a.T, a.d_model);
     if (gu == TILE_MIXED && mixed_wide_per_xcd(gate_up_tiles(bt, a.T, TILE_WIDE)) < 0) gu = TILE_WIDE;   // forced where it does not apply
-    hipError_t e = gu == TILE_WIDE     ? launch_gate_up<BM, MFMA_WM, 4>(a, bt)
-                   : gu == TILE_NARROW ? launch_gate_up<BM, MFMA_WM, 2>(a, bt)
-                   : gu == TILE_SMALL  ? launch_gate_up<BM_SMALL, SMALL_WM, 2>(a, bt)
-                   : gu == TILE_DEEP   ? launch_gate_up<BM_SMALL, SMALL_WM, 2, DEEP_D>(a, bt)
+    hipError_t e = gu == TILE_WIDE     ? launch_gate_up<ShapeWide>(a, bt)
+                   : gu == TILE_NARROW ? launch_gate_up<ShapeNarrow>(a, bt)
+                   : gu == TILE_SMALL  ? launch_gate_up<ShapeSmall>(a, bt)
+                   : gu == TILE_DEEP   ? launch_gate_up<ShapeDeep>(a, bt)
+                   : gu == TILE_SLIM   ? launch_gate_up<ShapeSlim>(a, bt)
                                        : launch_gate_up_mixed(a, bt);
     if (e != hipSuccess) return hipErrorLaunchFailure;
     return down_and_reduce<false>(a, bt, pl);

@@ -133,7 +133,7 @@ int forward_table(const BranchTable &bt, bool aligned, const void *x, const void
     if (path == MLPMOE_PATH_AUTO)
         path = !aligned ? MLPMOE_PATH_GENERIC : (T <= 16 ? MLPMOE_PATH_DECODE : MLPMOE_PATH_MFMA);
     int tile_shape = -1;
-    if (path >= MLPMOE_PATH_MFMA_WIDE && path <= MLPMOE_PATH_MFMA_DEEP) {
+    if (path >= MLPMOE_PATH_MFMA_WIDE && path <= MLPMOE_PATH_MFMA_SLIM) {
         tile_shape = path - MLPMOE_PATH_MFMA_WIDE;
         path = MLPMOE_PATH_MFMA;
         if (route && tile_shape >= 2) return MLPMOE_ERR_UNSUPPORTED;     // routed: 256-token tiles of one width
@@ -182,7 +182,7 @@ int forward_impl(const void *x, const void *Wg, const void *Wu, const void *Wd, 
 {
     int rc = validate_common(x, Wg, Wu, Wd, off, alpha, mask, T, d_model, d_inter, B, out);
     if (rc != MLPMOE_OK) return rc;
-    if (path < MLPMOE_PATH_AUTO || path > MLPMOE_PATH_MFMA_DEEP) return MLPMOE_ERR_UNSUPPORTED;
+    if (path < MLPMOE_PATH_AUTO || path > MLPMOE_PATH_MFMA_SLIM) return MLPMOE_ERR_UNSUPPORTED;
     if (T == 0) return MLPMOE_OK;
     BranchTable bt;
     build_table(off, alpha, mask, B, bt);
@@ -730,10 +730,10 @@ int mlpmoe_plan_create(const int32_t *branch_offsets, const float *alpha, const 
     p->max_T = max_T;
     p->aligned = elem_bytes == 2 && fast_path_aligned(p->bt, d_model, d_inter);
     // Workspace for every T up to max_T.  H grows with T; the split-K partials are T times a
-    // split factor that is constant while T stays inside one 256-token tile row, so the maximum
-    // over a tile row is at its last T: checking the multiples of 256 and max_T covers all.
+    // split factor that is constant while T stays inside one row of token tiles (64, 128 or 256 tokens),
+    // so the maximum over a tile row is at its last T: checking the multiples of 64 and max_T covers all.
     p->ws_bytes = 0;
-    for (long long t = 256; ; t += 256) {
+    for (long long t = 64; ; t += 64) {
         const int tt = t < max_T ? (int)t : max_T;
         p->ws_bytes = std::max(p->ws_bytes, mlpmoe_workspace_bytes(tt, d_model, d_inter, B, elem_bytes));
         if (tt == max_T) break;

@@ -164,7 +164,7 @@ def test_forward_argument_validation_needs_no_gpu():
     assert f(*(_fwd_args(off, al, mk) + [None, 0, mm.PATH_AUTO, None])) == mm.ERR_WORKSPACE
     assert f(*(_fwd_args(off, al, mk) + [ctypes.c_void_p(0x1000), 16, mm.PATH_AUTO, None])) == mm.ERR_WORKSPACE
     assert f(*(_fwd_args(off, al, mk) + [ctypes.c_void_p(0x1010), 1 << 30, mm.PATH_AUTO, None])) == mm.ERR_WORKSPACE
-    assert f(*(_fwd_args(off, al, mk) + [ctypes.c_void_p(0x1000), 1 << 30, 9, None])) == mm.ERR_UNSUPPORTED
+    assert f(*(_fwd_args(off, al, mk) + [ctypes.c_void_p(0x1000), 1 << 30, mm.PATH_MFMA_SLIM + 1, None])) == mm.ERR_UNSUPPORTED
     assert f(*(_fwd_args(off, al, mk, T=17) + [ctypes.c_void_p(0x1000), 1 << 30, mm.PATH_DECODE, None])) == mm.ERR_UNSUPPORTED
     odd = np.array([0, 60, 128, 192, 256], np.int32)      # branch boundary not a multiple of 8 ...
     mk2 = np.array([1, 0, 1, 1], np.uint8)                # ... and exposed as a run boundary

@@ -113,10 +113,11 @@ MFMA_TILE_CASES = MFMA_CASES + [
 
 @pytest.mark.parametrize("T,dm,off,mask", MFMA_TILE_CASES)
 def test_bf16_mfma_every_tile_shape(mm, T, dm, off, mask):
-    """Each tile shape of the MFMA kernels forced for both launches (256 x (128+128), 256 x (64+64), 128 x (64+64)):
+    """Each tile shape of the MFMA kernels forced for both launches (256 x (128+128), 256 x (64+64), 128 x (64+64)
+    with both ring depths, 64 x (64+64) with the staged ring):
     H and the result element by element, bitwise reproducible."""
     args = small_bf16_case(900 + T, T, dm, off, mask)
-    for p in (mm.PATH_MFMA_WIDE, mm.PATH_MFMA_NARROW, mm.PATH_MFMA_SMALL, mm.PATH_MFMA_DEEP):
+    for p in (mm.PATH_MFMA_WIDE, mm.PATH_MFMA_NARROW, mm.PATH_MFMA_SMALL, mm.PATH_MFMA_DEEP, mm.PATH_MFMA_SLIM):
         got, H = run_gpu_with_hidden(*args, path=p)
         check_bf16_flip_aware(got, H, *args, label="T=%d d_model=%d tile shape %d:" % (T, dm, p - mm.PATH_MFMA_WIDE))
         if sum(w for w, m in zip(np.diff(off), mask) if m) >= 1000:
@@ -362,7 +363,8 @@ def test_bf16_thin_layers_every_path(mm, T, dm, off, mask):
     """Layers with 8 .. 512 active neurons in contract AND exact mode on the generic, MFMA and decode kernels:
     the stored intermediate is compared element by element, and the outputs with the flips accounted for."""
     args = small_bf16_case(500 + T + dm, T, dm, off, mask)
-    paths = [mm.PATH_GENERIC, mm.PATH_MFMA, mm.PATH_MFMA_WIDE, mm.PATH_MFMA_NARROW, mm.PATH_MFMA_SMALL, mm.PATH_MFMA_DEEP] + (
+    paths = [mm.PATH_GENERIC, mm.PATH_MFMA, mm.PATH_MFMA_WIDE, mm.PATH_MFMA_NARROW, mm.PATH_MFMA_SMALL, mm.PATH_MFMA_DEEP,
+             mm.PATH_MFMA_SLIM] + (
         [mm.PATH_DECODE] if T <= 16 else [])
     for p in paths:
         got, H = run_gpu_with_hidden(*args, path=p)

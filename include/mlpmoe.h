@@ -315,17 +315,20 @@ MLPMOE_API int mlpmoe_forward_routed_f32_ws(const float *x, const float *W_gate,
  * absolute value is not strictly greater than it to zero (the entry times 0: it keeps its sign).
  * Branches with sparsity[b] <= 0, and empty branches, are left exactly as they are.
  *
- *   W_gate, W_up    device, bf16 (elem_bytes must be 2; MLPMOE_ERR_UNSUPPORTED otherwise),
- *                   16-byte aligned; d_model must be a multiple of 8 (MLPMOE_ERR_UNSUPPORTED)
+ *   W_gate, W_up    device, bf16 (elem_bytes 2, d_model a multiple of 8) or float (elem_bytes 4,
+ *                   d_model a multiple of 4), MLPMOE_ERR_UNSUPPORTED otherwise; 16-byte aligned.
+ *                   Float entries are compared as doubles with the threshold interpolated in
+ *                   double from the two neighbouring order statistics
  *   branch_offsets  host, B + 1 entries as for mlpmoe_forward
  *   sparsity        host, B doubles in [0, 1] (MLPMOE_ERR_SHAPE outside), or NULL for the
  *                   schedule of Sec. 3.2: s_b = 0.9 * b / B, branch 0 dense
  *   thresholds      host, 2 * B floats or NULL: [2b] gate, [2b+1] up; the interpolated quantile
- *                   (NaN for branches left alone)
+ *                   rounded to float (NaN for branches left alone)
  *   kept            host, 2 * B 64-bit counts or NULL: entries of the block that survive
  *                   (the block size for branches left alone)
- * Allocates and frees a device scratch buffer of B * 131088 bytes and synchronises `stream`
- * before it returns (this is offline weight preparation, not part of the forward).
+ * Allocates and frees a device scratch buffer of B * 131088 bytes (bf16) or B * 655424 bytes (float)
+ * and synchronises `stream` before it returns, for float storage also once in between (this is
+ * offline weight preparation, not part of the forward).
  * Not-a-number entries are not supported (their place in the order is undefined).
  */
 MLPMOE_API int mlpmoe_fade(void *W_gate, void *W_up, const int32_t *branch_offsets, const double *sparsity,
@@ -342,8 +345,9 @@ MLPMOE_API int mlpmoe_fade(void *W_gate, void *W_up, const int32_t *branch_offse
  * scores, equal scores in order of index.  The result feeds mlpmoe_slice (neuron_keep) and
  * mlpmoe_compact; the weights are not changed.
  *
- *   W_gate, W_up    device, bf16 row-major [d_inter, d_model] (elem_bytes must be 2 and d_model a
- *                   multiple of 8: MLPMOE_ERR_UNSUPPORTED otherwise), 16-byte aligned
+ *   W_gate, W_up    device, row-major [d_inter, d_model], bf16 (elem_bytes 2, d_model a multiple of 8)
+ *                   or float (elem_bytes 4, d_model a multiple of 4): MLPMOE_ERR_UNSUPPORTED
+ *                   otherwise; 16-byte aligned
  *   branch_offsets  host, B + 1 entries as for mlpmoe_forward
  *   keep_count      host, B entries, 0 <= keep_count[b] <= d_b (MLPMOE_ERR_SHAPE outside)
  *   neuron_keep     host, d_inter bytes: 1 = kept, 0 = dropped

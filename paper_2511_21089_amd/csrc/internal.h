@@ -47,9 +47,15 @@ extern thread_local char g_err_detail[192];
 hipError_t launch_fade_bf16(void *W, const int32_t *off, const double *sparsity, int B, int d_model,
                             uint32_t *scratch, uint32_t *host_result, int *job_of_branch, hipStream_t s);
 size_t fade_scratch_words(int B);
+// The same for a float matrix; thresholds / kept are per job (job_of_branch maps branches to jobs).
+hipError_t launch_fade_f32(void *W, const int32_t *off, const double *sparsity, int B, int d_model,
+                           uint32_t *scratch, double *thresholds, long long *kept, int *job_of_branch, hipStream_t s);
+size_t fade_scratch_words_f32(int B);
 // Structured form (whole neurons): scores and keep flags of all neurons, asynchronous on s.
-hipError_t launch_fade_neurons_bf16(const void *Wg, const void *Wu, const int32_t *off, const int32_t *keep_count,
-                                    int B, int d_model, int d_inter, double *scores, uint8_t *keep, hipStream_t s);
+// elem_bytes: 2 (bf16, d_model a multiple of 8) or 4 (float, a multiple of 4).
+hipError_t launch_fade_neurons(const void *Wg, const void *Wu, const int32_t *off, const int32_t *keep_count,
+                               int B, int d_model, int d_inter, int elem_bytes, double *scores, uint8_t *keep,
+                               hipStream_t s);
 
 // Records which runtime call failed and how (read back through mlpmoe_last_error_detail()).
 // Returns e, so that a failing site can `return note_hip_error("...", e);`.

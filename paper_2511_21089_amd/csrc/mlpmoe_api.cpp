@@ -433,13 +433,15 @@ int mlpmoe_fade(void *W_gate, void *W_up, const int32_t *branch_offsets, const d
     }
     if (d_inter == 0) return MLPMOE_OK;
     if (!W_gate || !W_up) return MLPMOE_ERR_NULL;
-    if (elem_bytes != 2 || d_model % 8 != 0) return MLPMOE_ERR_UNSUPPORTED;
+    // 16-byte pieces: 8 bf16 values or 4 floats per row piece
+    if ((elem_bytes != 2 && elem_bytes != 4) || d_model % (16 / elem_bytes) != 0) return MLPMOE_ERR_UNSUPPORTED;
     if (!aligned16(W_gate) || !aligned16(W_up)) return MLPMOE_ERR_ALIGN;
 
     (void)hipGetLastError();
     g_err_detail[0] = 0;
     uint32_t *scratch = nullptr;
-    hipError_t e = hipMalloc(reinterpret_cast<void **>(&scratch), fade_scratch_words(B) * sizeof(uint32_t));
+    const size_t scratch_words = elem_bytes == 2 ? fade_scratch_words(B) : fade_scratch_words_f32(B);
+    hipError_t e = hipMalloc(reinterpret_cast<void **>(&scratch), scratch_words * sizeof(uint32_t));
     if (e != hipSuccess) {
         (void)note_hip_error("hipMalloc(fade scratch)", e);
         (void)hipGetLastError();
@@ -448,8 +450,24 @@ int mlpmoe_fade(void *W_gate, void *W_up, const int32_t *branch_offsets, const d
     int rc = MLPMOE_OK;
     void *mats[2] = {W_gate, W_up};
     for (int m = 0; m < 2 && rc == MLPMOE_OK; ++m) {
-        uint32_t res[4 * MLPMOE_MAX_BRANCHES];
         int job[MLPMOE_MAX_BRANCHES];
+        if (elem_bytes == 4) {
+            double thr[MLPMOE_MAX_BRANCHES];
+            long long cnt[MLPMOE_MAX_BRANCHES];
+            e = launch_fade_f32(mats[m], branch_offsets, sched, B, d_model, scratch, thr, cnt, job,
+                                static_cast<hipStream_t>(stream));
+            if (e != hipSuccess) {
+                rc = MLPMOE_ERR_HIP;
+                break;
+            }
+            for (int b = 0; b < B; ++b) {
+                if (job[b] < 0) continue;
+                if (thresholds) thresholds[2 * b + m] = (float)thr[job[b]];
+                if (kept) kept[2 * b + m] = cnt[job[b]];
+            }
+            continue;
+        }
+        uint32_t res[4 * MLPMOE_MAX_BRANCHES];
         e = launch_fade_bf16(mats[m], branch_offsets, sched, B, d_model, scratch, res, job,
                              static_cast<hipStream_t>(stream));
         if (e != hipSuccess) {
@@ -487,7 +505,7 @@ int mlpmoe_fade_neurons(const void *W_gate, const void *W_up, const int32_t *bra
     }
     if (d_inter == 0) return MLPMOE_OK;
     if (!W_gate || !W_up || !neuron_keep) return MLPMOE_ERR_NULL;
-    if (elem_bytes != 2 || d_model % 8 != 0) return MLPMOE_ERR_UNSUPPORTED;
+    if ((elem_bytes != 2 && elem_bytes != 4) || d_model % (16 / elem_bytes) != 0) return MLPMOE_ERR_UNSUPPORTED;
     if (!aligned16(W_gate) || !aligned16(W_up)) return MLPMOE_ERR_ALIGN;
 
     (void)hipGetLastError();
@@ -503,7 +521,7 @@ int mlpmoe_fade_neurons(const void *W_gate, const void *W_up, const int32_t *bra
     }
     double *d_scores = reinterpret_cast<double *>(scratch);
     uint8_t *d_keep = reinterpret_cast<uint8_t *>(scratch + score_bytes);
-    e = launch_fade_neurons_bf16(W_gate, W_up, branch_offsets, keep_count, B, d_model, d_inter, d_scores, d_keep, s);
+    e = launch_fade_neurons(W_gate, W_up, branch_offsets, keep_count, B, d_model, d_inter, elem_bytes, d_scores, d_keep, s);
     if (e == hipSuccess) {
         e = hipMemcpyAsync(neuron_keep, d_keep, (size_t)d_inter, hipMemcpyDeviceToHost, s);
         if (e == hipSuccess && scores)

@@ -229,8 +229,9 @@ def test_fade_argument_validation():
     assert call(np.array([0, 9, 8], np.int32), None, 64, 8, 2, 2) == mm.ERR_OFFSETS
     assert call(off, np.array([0.0, 1.5]), 64, 16, 2, 2) == mm.ERR_SHAPE
     assert call(off, np.array([0.0, float("nan")]), 64, 16, 2, 2) == mm.ERR_SHAPE
-    assert call(off, None, 64, 16, 2, 4) == mm.ERR_UNSUPPORTED          # float storage
-    assert call(off, None, 60, 16, 2, 2) == mm.ERR_UNSUPPORTED          # d_model not a multiple of 8
+    assert call(off, None, 64, 16, 2, 8) == mm.ERR_UNSUPPORTED          # neither bf16 nor float storage
+    assert call(off, None, 60, 16, 2, 2) == mm.ERR_UNSUPPORTED          # bf16: d_model not a multiple of 8
+    assert call(off, None, 62, 16, 2, 4) == mm.ERR_UNSUPPORTED          # float: not a multiple of 4
     assert call(off, None, 64, 16, 2, 2, ctypes.c_void_p(0x1004)) == mm.ERR_ALIGN
     assert call(off, None, 64, 16, 2, 2, None) == mm.ERR_NULL
     # nothing to do: d_inter == 0 is accepted without pointers
@@ -253,8 +254,9 @@ def test_fade_neurons_argument_validation():
     assert call(off, None, 64, 16, 2, 2) == mm.ERR_NULL
     assert call(off, np.array([9, 3], np.int32), 64, 16, 2, 2) == mm.ERR_SHAPE      # more than the branch holds
     assert call(off, np.array([8, -1], np.int32), 64, 16, 2, 2) == mm.ERR_SHAPE
-    assert call(off, cnt, 64, 16, 2, 4) == mm.ERR_UNSUPPORTED
+    assert call(off, cnt, 64, 16, 2, 1) == mm.ERR_UNSUPPORTED
     assert call(off, cnt, 60, 16, 2, 2) == mm.ERR_UNSUPPORTED
+    assert call(off, cnt, 62, 16, 2, 4) == mm.ERR_UNSUPPORTED
     assert call(off, cnt, 64, 16, 2, 2, ctypes.c_void_p(0x1008)) == mm.ERR_ALIGN
     assert call(off, cnt, 64, 16, 2, 2, None) == mm.ERR_NULL
     assert call(off, cnt, 64, 16, 2, 2, fake, None) == mm.ERR_NULL

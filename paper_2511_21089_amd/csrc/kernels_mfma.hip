@@ -830,17 +830,39 @@ route_tile_list(const uint8_t *__restrict__ route, uint8_t *__restrict__ tile_ne
 }
 
 // out[i] = sum_z partial[z][i], summed in z order: deterministic.  out_bf16: out holds bf16 values.
-__global__ void reduce_partials(const float *__restrict__ partial, float *__restrict__ out, size_t n,
-                                int splits, int out_bf16)
+// n4 = pieces of four values (T * d_model is a multiple of 8 on this path; partial is 256-byte, out 16-byte
+// aligned).  Two pieces per thread and trip, so that 2 * splits loads are in flight per thread.
+__global__ void __launch_bounds__(256)
+reduce_partials(const float *__restrict__ partial, float *__restrict__ out, size_t n4, int splits, int out_bf16)
 {
-    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n;
-         i += (size_t)gridDim.x * blockDim.x) {
-        float s = partial[i];
-        for (int z = 1; z < splits; ++z) s += partial[(size_t)z * n + i];
-        if (out_bf16)
-            reinterpret_cast<uint16_t *>(out)[i] = to_bf16(s);
-        else
-            out[i] = s;
+    const f32x4 *p4 = reinterpret_cast<const f32x4 *>(partial);
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n4; i += 2 * stride) {
+        const size_t j = i + stride;
+        const bool two = j < n4;
+        f32x4 s0 = p4[i], s1 = two ? p4[j] : f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int z = 1; z < splits; ++z) {
+            const f32x4 a = p4[(size_t)z * n4 + i];
+            const f32x4 b = two ? p4[(size_t)z * n4 + j] : f32x4{0.f, 0.f, 0.f, 0.f};
+            s0 += a;
+            s1 += b;
+        }
+        if (out_bf16) {
+            u32x2 *o = reinterpret_cast<u32x2 *>(out);
+            u32x2 pk;
+            pk.x = (uint32_t)to_bf16(s0[0]) | ((uint32_t)to_bf16(s0[1]) << 16);
+            pk.y = (uint32_t)to_bf16(s0[2]) | ((uint32_t)to_bf16(s0[3]) << 16);
+            o[i] = pk;
+            if (two) {
+                pk.x = (uint32_t)to_bf16(s1[0]) | ((uint32_t)to_bf16(s1[1]) << 16);
+                pk.y = (uint32_t)to_bf16(s1[2]) | ((uint32_t)to_bf16(s1[3]) << 16);
+                o[j] = pk;
+            }
+        } else {
+            f32x4 *o = reinterpret_cast<f32x4 *>(out);
+            o[i] = s0;
+            if (two) o[j] = s1;
+        }
     }
 }
 
@@ -1106,10 +1128,10 @@ static hipError_t down_and_reduce(const FwdArgs &a, const BranchTable &bt, const
     if (e != hipSuccess) return hipErrorLaunchFailure;
     if (pl.splits > 1) {
         ProfileScope ps(MLPMOE_KERNEL_SPLITK_REDUCE, a.stream);
-        const size_t n = (size_t)a.T * a.d_model;
-        size_t blocks = (n + 255) / 256;
-        if (blocks > 8192) blocks = 8192;
-        reduce_partials<<<(unsigned)blocks, 256, 0, a.stream>>>(a.partial, a.out, n, pl.splits, a.out_bf16 ? 1 : 0);
+        const size_t n4 = (size_t)a.T * a.d_model / 4;
+        size_t blocks = (n4 + 511) / 512;
+        if (blocks > 4096) blocks = 4096;
+        reduce_partials<<<(unsigned)blocks, 256, 0, a.stream>>>(a.partial, a.out, n4, pl.splits, a.out_bf16 ? 1 : 0);
     }
     return launch_status("reduce_partials launch");
 }

@@ -80,7 +80,7 @@ def build_layer(mm, synth, name, T, seed):
     """Synthetic layer -> device tensors + branch table (+ host copies for the oracle)."""
     L = synth.make_layer(name, T, seed=seed)
     w = L.workload
-    off, _, mask, gather = mm.mlpmoe_slice(w.d_inter, w.B, 0, L.neuron_keep, 8)
+    off, _, mask, gather = mm.mlpmoe_slice(w.d_inter, w.B, 0, L.neuron_keep, 8, 64)
     mask = mask.copy()
     mask[L.inactive] = 0
     alpha = L.alpha_draw

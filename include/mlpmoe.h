@@ -118,6 +118,21 @@ MLPMOE_API int mlpmoe_slice(int d_inter, int B, int K_keep, const uint8_t *neuro
                  int32_t *gather_index, int gather_capacity);
 
 /*
+ * mlpmoe_slice_rows -- mlpmoe_slice (Sec. 3.1 slicing, Sec. 3.3 rule, compaction of kept neurons) with
+ * one more kind of padding: after every branch has been rounded up to a multiple of pad_to, the row
+ * count of the whole compacted layer is rounded up to a multiple of pad_rows_to (1 .. 4096) with
+ * further padding rows at the end of the LAST branch (gather index -1).  That row count is the
+ * leading dimension of the compacted W_down: a multiple of 64 makes every row of a bf16 W_down
+ * start on a 128-byte line, which the kernels' row-piece loads want (an 8B-shaped layer compacted
+ * to 11544 rows: the decode down projection takes 28.1 us at T = 16 as it is and 24.5 us with 11584
+ * rows).  gather_capacity: d_inter + B*(pad_to-1) + pad_rows_to-1 always suffices.  Everything else
+ * as for mlpmoe_slice, which is this call with pad_rows_to = 1.
+ */
+MLPMOE_API int mlpmoe_slice_rows(int d_inter, int B, int K_keep, const uint8_t *neuron_keep, int pad_to,
+                                 int pad_rows_to, int32_t *branch_offsets, float *alpha, uint8_t *active_mask,
+                                 int32_t *gather_index, int gather_capacity);
+
+/*
  * mlpmoe_compact -- applies a gather list on the device (weight preparation, not
  * part of the per-token path).  For r in [0, n_rows):
  *     W_gate_c[r, :] = gather[r] >= 0 ? W_gate[gather[r], :] : 0      (same for W_up)

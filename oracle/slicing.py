@@ -36,12 +36,16 @@ def fade_sparsity(i: int, B: int) -> float:
     return 0.9 * i / B
 
 
-def slice_plan(d_inter, B, K_keep=0, neuron_keep=None, pad_to=1):
-    """Reference for the library's slicing call.
+def slice_plan(d_inter, B, K_keep=0, neuron_keep=None, pad_to=1, pad_rows_to=1):
+    """Reference for the library's slicing calls.
 
     Returns (offsets[B+1], alpha[B], mask[B], gather) where gather lists, for
     every row of the compacted layer, the source neuron index or -1 for a
-    zero padding row that rounds a branch up to a multiple of pad_to.
+    zero padding row that rounds a branch up to a multiple of pad_to; the row
+    count of the whole layer is then rounded up to a multiple of pad_rows_to
+    with more zero rows at the end of the last branch.  (Padding is a storage
+    convenience of this implementation, not part of the method: a zero gate/up
+    row with a zero down column adds exactly nothing to the sum of Sec. 3.1.)
     """
     sizes = split_sizes(d_inter, B)
     if K_keep and 0 < K_keep < B:
@@ -62,6 +66,9 @@ def slice_plan(d_inter, B, K_keep=0, neuron_keep=None, pad_to=1):
         gather.extend(idx + [-1] * (padded - n))
         offsets.append(offsets[-1] + padded)
         start += sizes[b]
+    extra = (-offsets[-1]) % pad_rows_to
+    gather.extend([-1] * extra)
+    offsets[-1] += extra
     return (np.asarray(offsets, dtype=np.int32), np.asarray(alpha, dtype=np.float32),
             np.asarray(mask, dtype=np.uint8), np.asarray(gather, dtype=np.int32))
 

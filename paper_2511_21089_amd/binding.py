@@ -23,7 +23,7 @@ PATH_AUTO, PATH_GENERIC, PATH_MFMA, PATH_DECODE = 0, 1, 2, 3
 PATH_MFMA_WIDE, PATH_MFMA_NARROW, PATH_MFMA_SMALL, PATH_MFMA_MIXED, PATH_MFMA_DEEP, PATH_MFMA_SLIM = 4, 5, 6, 7, 8, 9
 MAX_BRANCHES = 64
 
-EXPORTS = ["mlpmoe_status_string", "mlpmoe_last_error_detail", "mlpmoe_slice", "mlpmoe_compact", "mlpmoe_fade", "mlpmoe_fade_neurons", "mlpmoe_workspace_bytes",
+EXPORTS = ["mlpmoe_status_string", "mlpmoe_last_error_detail", "mlpmoe_slice", "mlpmoe_slice_rows", "mlpmoe_compact", "mlpmoe_fade", "mlpmoe_fade_neurons", "mlpmoe_workspace_bytes",
            "mlpmoe_forward_bf16", "mlpmoe_forward", "mlpmoe_forward_f32", "mlpmoe_forward_bf16_ws",
            "mlpmoe_forward_f32_ws", "mlpmoe_release", "mlpmoe_profile_enable",
            "mlpmoe_profile_collect", "mlpmoe_profile_disable", "mlpmoe_plan_create", "mlpmoe_plan_forward",
@@ -63,6 +63,8 @@ def _load() -> ctypes.CDLL:
     lib.mlpmoe_last_error_detail.restype = ctypes.c_char_p
     lib.mlpmoe_slice.argtypes = [i, i, i, bp, i, ip, fp, bp, ip, i]
     lib.mlpmoe_slice.restype = i
+    lib.mlpmoe_slice_rows.argtypes = [i, i, i, bp, i, i, ip, fp, bp, ip, i]
+    lib.mlpmoe_slice_rows.restype = i
     lib.mlpmoe_compact.argtypes = [vp, vp, vp, vp, i, i, i, i, vp, vp, vp, vp]
     lib.mlpmoe_compact.restype = i
     lib.mlpmoe_plan_create.argtypes = [ip, fp, bp, i, i, i, i, i, ctypes.POINTER(ctypes.c_void_p)]
@@ -148,20 +150,26 @@ def _stream_ptr(stream):
 
 
 # --------------------------------------------------------------------------- host-only
-def mlpmoe_slice(d_inter: int, B: int, K_keep: int = 0, neuron_keep=None, pad_to: int = 1):
-    """Branch table of one MLP.  Returns (branch_offsets[B+1], alpha[B], active_mask[B], gather_index)."""
+def mlpmoe_slice(d_inter: int, B: int, K_keep: int = 0, neuron_keep=None, pad_to: int = 1, pad_rows_to: int = 1):
+    """Branch table of one MLP.  Returns (branch_offsets[B+1], alpha[B], active_mask[B], gather_index).
+    pad_rows_to > 1 goes through mlpmoe_slice_rows (row count of the compacted layer rounded up)."""
     n = max(int(B), 0)
     off = np.zeros(n + 1, dtype=np.int32)
     alpha = np.zeros(n, dtype=np.float32)
     mask = np.zeros(n, dtype=np.uint8)
-    cap = max(int(d_inter), 0) + n * max(int(pad_to) - 1, 0)
+    cap = max(int(d_inter), 0) + n * max(int(pad_to) - 1, 0) + max(int(pad_rows_to) - 1, 0)
     gather = np.full(max(cap, 1), -2, dtype=np.int32)
     keep = None if neuron_keep is None else _host(neuron_keep, np.uint8)
     if keep is not None and keep.shape != (d_inter,):
         raise ValueError("neuron_keep must have d_inter entries")
-    rc = lib.mlpmoe_slice(int(d_inter), int(B), int(K_keep), None if keep is None else keep.ctypes.data,
-                          int(pad_to), off.ctypes.data, alpha.ctypes.data, mask.ctypes.data,
-                          gather.ctypes.data, cap)
+    if int(pad_rows_to) == 1:
+        rc = lib.mlpmoe_slice(int(d_inter), int(B), int(K_keep), None if keep is None else keep.ctypes.data,
+                              int(pad_to), off.ctypes.data, alpha.ctypes.data, mask.ctypes.data,
+                              gather.ctypes.data, cap)
+    else:
+        rc = lib.mlpmoe_slice_rows(int(d_inter), int(B), int(K_keep), None if keep is None else keep.ctypes.data,
+                                   int(pad_to), int(pad_rows_to), off.ctypes.data, alpha.ctypes.data,
+                                   mask.ctypes.data, gather.ctypes.data, cap)
     _check(rc, "mlpmoe_slice")
     return off, alpha, mask, gather[: int(off[-1])].copy()
 

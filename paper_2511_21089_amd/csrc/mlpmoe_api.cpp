@@ -372,9 +372,17 @@ int mlpmoe_slice(int d_inter, int B, int K_keep, const uint8_t *neuron_keep, int
                  int32_t *branch_offsets, float *alpha, uint8_t *active_mask, int32_t *gather_index,
                  int gather_capacity)
 {
+    return mlpmoe_slice_rows(d_inter, B, K_keep, neuron_keep, pad_to, 1, branch_offsets, alpha, active_mask,
+                             gather_index, gather_capacity);
+}
+
+int mlpmoe_slice_rows(int d_inter, int B, int K_keep, const uint8_t *neuron_keep, int pad_to, int pad_rows_to,
+                      int32_t *branch_offsets, float *alpha, uint8_t *active_mask, int32_t *gather_index,
+                      int gather_capacity)
+{
     if (!branch_offsets || !alpha || !active_mask) return MLPMOE_ERR_NULL;
     if (B < 1 || B > MLPMOE_MAX_BRANCHES || d_inter < 0 || d_inter > (1 << 24) || pad_to < 1 ||
-        pad_to > 4096 || K_keep < 0)
+        pad_to > 4096 || pad_rows_to < 1 || pad_rows_to > 4096 || K_keep < 0)
         return MLPMOE_ERR_SHAPE;
     if (gather_index && gather_capacity < 0) return MLPMOE_ERR_SHAPE;
 
@@ -411,6 +419,14 @@ int mlpmoe_slice(int d_inter, int B, int K_keep, const uint8_t *neuron_keep, int
         dst += padded;
         branch_offsets[b + 1] = dst;
     }
+    // the compacted layer's row count (the leading dimension of its W_down) rounded up: more padding rows at
+    // the end of the last branch
+    const int total = (dst + pad_rows_to - 1) / pad_rows_to * pad_rows_to;
+    if (gather_index) {
+        if (total > gather_capacity) return MLPMOE_ERR_SHAPE;
+        for (int r = dst; r < total; ++r) gather_index[r] = -1;
+    }
+    branch_offsets[B] = total;
     return MLPMOE_OK;
 }
 

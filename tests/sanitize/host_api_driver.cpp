@@ -33,6 +33,22 @@ int main()
                             mlpmoe_slice(d_inter, B, K, with_keep ? keep.data() : nullptr, pad, off.data(), alpha.data(),
                                          mask.data(), gather.data(), off[B] - 1) != MLPMOE_ERR_SHAPE)
                             ++bad;
+                        // the row count rounded up as well: exact capacity accepted, one entry less refused
+                        const int rows_to = 64, cap_r = cap + rows_to - 1;
+                        std::vector<int32_t> gather_r(cap_r);
+                        rc = mlpmoe_slice_rows(d_inter, B, K, with_keep ? keep.data() : nullptr, pad, rows_to, off.data(),
+                                               alpha.data(), mask.data(), gather_r.data(), cap_r);
+                        if (rc != MLPMOE_OK || off[B] % rows_to || off[B] > cap_r) ++bad;
+                        const int need = off[B];
+                        if (need > 0) {
+                            std::vector<int32_t> exact(need);
+                            if (mlpmoe_slice_rows(d_inter, B, K, with_keep ? keep.data() : nullptr, pad, rows_to, off.data(),
+                                                  alpha.data(), mask.data(), exact.data(), need) != MLPMOE_OK)
+                                ++bad;
+                            if (mlpmoe_slice_rows(d_inter, B, K, with_keep ? keep.data() : nullptr, pad, rows_to, off.data(),
+                                                  alpha.data(), mask.data(), exact.data(), need - 1) != MLPMOE_ERR_SHAPE)
+                                ++bad;
+                        }
                     }
                 }
     // validation of the forward entry points: errors are reported before any device access

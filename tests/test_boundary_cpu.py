@@ -82,6 +82,15 @@ def test_slice_matches_oracle(d_inter, B, K, pad):
         assert np.array_equal(gather, o_gather)
         assert np.allclose(alpha, o_alpha, rtol=1e-7, atol=0)
         assert np.all(np.diff(off) % pad == 0)
+        # the row count of the whole layer rounded up as well: more padding rows at the end of the last branch
+        for rows_to in (64, 5):
+            off_r, alpha_r, mask_r, gather_r = mm.mlpmoe_slice(d_inter, B, K, keep, pad, rows_to)
+            o_off, _, _, o_gather = oracle.slice_plan(d_inter, B, K, keep, pad, rows_to)
+            assert np.array_equal(off_r, o_off) and np.array_equal(gather_r, o_gather)
+            assert off_r[-1] % rows_to == 0 and 0 <= off_r[-1] - off[-1] < rows_to
+            assert np.array_equal(off_r[:-1], off[:-1]) and np.array_equal(gather_r[:len(gather)], gather)
+            assert np.all(gather_r[len(gather):] == -1)
+            assert np.array_equal(alpha_r, alpha) and np.array_equal(mask_r, mask)
 
 
 def test_slice_compensated_alpha_closed_form():
@@ -98,6 +107,12 @@ def test_slice_errors():
     assert f(16, 0, 0, None, 1, off.ctypes.data, al.ctypes.data, mk.ctypes.data, None, 0) == mm.ERR_SHAPE
     assert f(16, 65, 0, None, 1, off.ctypes.data, al.ctypes.data, mk.ctypes.data, None, 0) == mm.ERR_SHAPE
     assert f(-1, 4, 0, None, 1, off.ctypes.data, al.ctypes.data, mk.ctypes.data, None, 0) == mm.ERR_SHAPE
+    g = mm.lib.mlpmoe_slice_rows
+    assert g(16, 4, 0, None, 1, 0, off.ctypes.data, al.ctypes.data, mk.ctypes.data, None, 0) == mm.ERR_SHAPE
+    assert g(16, 4, 0, None, 1, 4097, off.ctypes.data, al.ctypes.data, mk.ctypes.data, None, 0) == mm.ERR_SHAPE
+    small = np.zeros(17, np.int32)       # 16 rows rounded up to 64 do not fit 17 entries
+    assert g(16, 4, 0, None, 1, 64, off.ctypes.data, al.ctypes.data, mk.ctypes.data, small.ctypes.data, 17) == mm.ERR_SHAPE
+    assert g(16, 4, 0, None, 1, 64, off.ctypes.data, al.ctypes.data, mk.ctypes.data, None, 0) == mm.OK and off[4] == 64
     assert f(16, 4, 0, None, 0, off.ctypes.data, al.ctypes.data, mk.ctypes.data, None, 0) == mm.ERR_SHAPE
     g = np.zeros(8, np.int32)
     assert f(16, 4, 0, None, 1, off.ctypes.data, al.ctypes.data, mk.ctypes.data, g.ctypes.data, 8) == mm.ERR_SHAPE

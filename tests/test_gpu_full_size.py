@@ -13,9 +13,9 @@ from paper_2511_21089_amd import synth
 pytestmark = pytest.mark.gpu
 
 
-def table_for(L, mm, pad_to=8):
+def table_for(L, mm, pad_to=8, pad_rows_to=64):
     w = L.workload
-    off, alpha, mask, gather = mm.mlpmoe_slice(w.d_inter, w.B, 0, L.neuron_keep, pad_to)
+    off, alpha, mask, gather = mm.mlpmoe_slice(w.d_inter, w.B, 0, L.neuron_keep, pad_to, pad_rows_to)
     mask = mask.copy()
     mask[L.inactive] = 0
     return off, L.alpha_draw, mask, gather

@@ -371,6 +371,28 @@ def test_slice_plan_gather_and_padding():
     off, _, _, gather = oracle.slice_plan(10, 3, 0, keep, pad_to=1)
     # widths 4,3,3 -> kept 3,1,2
     assert list(off) == [0, 3, 4, 6] and list(gather) == [0, 2, 3, 6, 7, 8]
+    # the row count of the whole layer rounded up to a multiple of 4: two more padding rows in the last branch
+    off, _, _, gather = oracle.slice_plan(10, 3, 0, keep, pad_to=1, pad_rows_to=4)
+    assert list(off) == [0, 3, 4, 8] and list(gather) == [0, 2, 3, 6, 7, 8, -1, -1]
+    off, _, _, gather = oracle.slice_plan(10, 2, 0, keep, pad_to=4, pad_rows_to=8)
+    assert list(off) == [0, 4, 8] and len(gather) == 8          # already a multiple: nothing added
+
+
+def test_row_padding_adds_nothing_to_the_forward():
+    """Rounding the compacted layer's row count up (pad_rows_to) appends zero rows / columns: the forward of the
+    padded compacted layer equals, exactly, the forward of the layer compacted without it."""
+    rng = np.random.default_rng(17)
+    d_model, d_inter, B, T = 24, 90, 5, 6
+    Wg, Wu = rng.standard_normal((d_inter, d_model)), rng.standard_normal((d_inter, d_model))
+    Wd, x = rng.standard_normal((d_model, d_inter)), rng.standard_normal((T, d_model))
+    keep = (rng.uniform(size=d_inter) < 0.6).astype(np.uint8)
+    alpha = rng.uniform(0.9, 1.2, B).astype(np.float32)
+    outs = []
+    for rows_to in (1, 64):
+        off, _, mask, gather = oracle.slice_plan(d_inter, B, 0, keep, 8, rows_to)
+        assert off[-1] % rows_to == 0
+        outs.append(oracle.mlpmoe_forward(x, *oracle.compact_layer(Wg, Wu, Wd, gather), off, alpha, mask))
+    assert np.array_equal(outs[0], outs[1])
 
 
 def test_fade_workload_widths():

@@ -13,7 +13,8 @@
 // Both kernels share one main loop: BMT A rows (tokens) against two blocks of 32 NB B rows, waves in
 // a WM x 2 arrangement, each wave owning (BMT / WM) x (16 NB + 16 NB) outputs as 16x16 MFMA tiles.
 // Tile shapes in use: 256 x (128 + 128) and 256 x (64 + 64) with 8 waves and the whole LDS of a CU,
-// 128 x (64 + 64) with 4 waves and either half the LDS (two workgroups per CU) or a deeper ring.  The
+// 128 x (64 + 64) with 4 waves and either half the LDS (two workgroups per CU) or a deeper ring,
+// 64 x (64 + 64) with 4 waves and a ring of whole K tiles (five requested ahead).  The
 // 16x16x32 shape is used rather than 32x32x16 because the chip is power limited on this work: with
 // random operands a pure stream of 16x16x32 MFMAs sustains 2.0 PFLOP/s, one of 32x32x16 1.7.
 #include <algorithm>

@@ -37,7 +37,7 @@ TRAFFIC = {
     # (workload, kernel): (sha256 of the kernel's source file, bytes per launch = read + written, summary file)
     # gate_up_mfma at T=4096: 1409.4 MB read (x is re-read once per group of 4 neuron tiles and the
     # weights once per XCD that needs them: 5.3x the 268 MB the kernel has to read) + 117.5 MB written
-    ("llama8b_T4096", "gate_up_mfma"): ("c8c036a710ff98705f2efb515328a7ddf0f2c4ea8e7d9fb6a109815fcea16dd4", 1526.9e6,
+    ("llama8b_T4096", "gate_up_mfma"): ("23043a12f8aa268e1979e59db3bc4d130e2fa22bed6180a57a9ab145711f132a", 1526.9e6,
                                         "profiles/bench_llama8b_T4096_hbm_counters.md"),
     # decode gate+up at T=1: 235.8 MB read (the weights, once) + 0.1 MB written
     ("llama8b_T1", "decode_gate_up"): ("975659ba3cb068270946adf36a755d8bbb024b21a506aa9bb78ec2c0d8d2a01c", 235.9e6,

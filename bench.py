@@ -305,6 +305,39 @@ def others(mm, synth, torch, seed):
                                         "algorithmic_bytes": 3 * touched,   # read, read again, write
                                         "gbs": round(3 * touched / best / 1e9, 1),
                                         "hbm_frac": round(3 * touched / best / 1e9 / HBM_PEAK_GBS, 4)}
+            # Context only, not part of the path: the two plain GEMMs of this layer (no SiLU*up pass, no branch
+            # table, bf16 results) through the vendor library as PyTorch calls it, timed with events in the same
+            # process on the same weights and activations at T = 4096; boxes differ by more than the margin
+            # between the two, so the comparison is only meaningful inside one run.
+            Tl = 4096
+            xl = torch.randn(Tl, w.d_model, device="cuda").to(torch.bfloat16)
+            Wgu = torch.cat([dev[0], dev[1]])
+            hl = (torch.randn(Tl, w.d_inter, device="cuda") * 0.5).to(torch.bfloat16)
+            o1 = torch.empty(Tl, 2 * w.d_inter, device="cuda", dtype=torch.bfloat16)
+            o2 = torch.empty(Tl, w.d_model, device="cuda", dtype=torch.bfloat16)
+
+            def lib_step():
+                torch.mm(xl, Wgu.t(), out=o1)
+                torch.mm(hl, dev[2].t(), out=o2)
+
+            t_end = time.perf_counter() + PREWARM_S
+            while time.perf_counter() < t_end:
+                for _ in range(4):
+                    lib_step()
+                torch.cuda.synchronize()
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(3 * 20)]
+            for k in range(20):
+                ev[3 * k].record()
+                torch.mm(xl, Wgu.t(), out=o1)
+                ev[3 * k + 1].record()
+                torch.mm(hl, dev[2].t(), out=o2)
+                ev[3 * k + 2].record()
+            torch.cuda.synchronize()
+            res["llama8b_T4096_library_gemms"] = {
+                "gate_up_us": round(sum(ev[3 * k].elapsed_time(ev[3 * k + 1]) for k in range(20)) / 20 * 1e3, 1),
+                "down_us": round(sum(ev[3 * k + 1].elapsed_time(ev[3 * k + 2]) for k in range(20)) / 20 * 1e3, 1),
+                "what": "torch.mm x2 on the same layer (plain GEMMs, context only)"}
+            del Wgu, hl, xl, o1, o2
         del x, dev
         torch.cuda.empty_cache()
     return res

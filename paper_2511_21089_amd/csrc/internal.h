@@ -37,7 +37,7 @@ struct FwdArgs {
     size_t partial_bytes;
     const uint8_t *route = nullptr;   // per-token routing [T, B] (device), or nullptr
     uint8_t *route_scratch = nullptr; // route_scratch_bytes(T, d_inter) bytes for the routed MFMA path (device)
-    int tile_shape = -1;              // MFMA kernels: -1 = chosen from the sizes, else 0 wide / 1 narrow / 2 small
+    int tile_shape = -1;              // MFMA kernels: -1 = chosen from the sizes, else a TileShape (MLPMOE_PATH_MFMA_* - MLPMOE_PATH_MFMA_WIDE)
     hipStream_t stream;
 };
 

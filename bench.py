@@ -194,6 +194,33 @@ def cpu_baseline(synth, L, host, off, alpha, mask, seconds):
             "sample": "first %d of %d tokens of the same batch, exact fp64 mode, %.1f s" % (n, L.T, dt)}
 
 
+def library_gemms(torch, Wgu, Wd, T):
+    """x @ [W_gate; W_up]^T and h @ W_down^T as two torch.mm calls, per-call time from events."""
+    d_model, d_inter = Wd.shape
+    x = torch.randn(T, d_model, device="cuda").to(torch.bfloat16)
+    h = (torch.randn(T, d_inter, device="cuda") * 0.5).to(torch.bfloat16)
+    o1 = torch.empty(T, 2 * d_inter, device="cuda", dtype=torch.bfloat16)
+    o2 = torch.empty(T, d_model, device="cuda", dtype=torch.bfloat16)
+    t_end = time.perf_counter() + PREWARM_S
+    while time.perf_counter() < t_end:
+        for _ in range(4):
+            torch.mm(x, Wgu.t(), out=o1)
+            torch.mm(h, Wd.t(), out=o2)
+        torch.cuda.synchronize()
+    n = 20
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3 * n)]
+    for k in range(n):
+        ev[3 * k].record()
+        torch.mm(x, Wgu.t(), out=o1)
+        ev[3 * k + 1].record()
+        torch.mm(h, Wd.t(), out=o2)
+        ev[3 * k + 2].record()
+    torch.cuda.synchronize()
+    return {"gate_up_us": round(sum(ev[3 * k].elapsed_time(ev[3 * k + 1]) for k in range(n)) / n * 1e3, 1),
+            "down_us": round(sum(ev[3 * k + 1].elapsed_time(ev[3 * k + 2]) for k in range(n)) / n * 1e3, 1),
+            "what": "torch.mm x2 on the same layer (plain GEMMs, context only)"}
+
+
 def others(mm, synth, torch, seed):
     """Short runs of the remaining workloads: tokens/s and the fraction of the roofline that bounds them."""
     res = {}
@@ -307,37 +334,12 @@ def others(mm, synth, torch, seed):
                                         "hbm_frac": round(3 * touched / best / 1e9 / HBM_PEAK_GBS, 4)}
             # Context only, not part of the path: the two plain GEMMs of this layer (no SiLU*up pass, no branch
             # table, bf16 results) through the vendor library as PyTorch calls it, timed with events in the same
-            # process on the same weights and activations at T = 4096; boxes differ by more than the margin
-            # between the two, so the comparison is only meaningful inside one run.
-            Tl = 4096
-            xl = torch.randn(Tl, w.d_model, device="cuda").to(torch.bfloat16)
+            # process on the same weights at the prefill sizes timed above; boxes differ by more than the
+            # margin between the two, so the comparison is only meaningful inside one run.
             Wgu = torch.cat([dev[0], dev[1]])
-            hl = (torch.randn(Tl, w.d_inter, device="cuda") * 0.5).to(torch.bfloat16)
-            o1 = torch.empty(Tl, 2 * w.d_inter, device="cuda", dtype=torch.bfloat16)
-            o2 = torch.empty(Tl, w.d_model, device="cuda", dtype=torch.bfloat16)
-
-            def lib_step():
-                torch.mm(xl, Wgu.t(), out=o1)
-                torch.mm(hl, dev[2].t(), out=o2)
-
-            t_end = time.perf_counter() + PREWARM_S
-            while time.perf_counter() < t_end:
-                for _ in range(4):
-                    lib_step()
-                torch.cuda.synchronize()
-            ev = [torch.cuda.Event(enable_timing=True) for _ in range(3 * 20)]
-            for k in range(20):
-                ev[3 * k].record()
-                torch.mm(xl, Wgu.t(), out=o1)
-                ev[3 * k + 1].record()
-                torch.mm(hl, dev[2].t(), out=o2)
-                ev[3 * k + 2].record()
-            torch.cuda.synchronize()
-            res["llama8b_T4096_library_gemms"] = {
-                "gate_up_us": round(sum(ev[3 * k].elapsed_time(ev[3 * k + 1]) for k in range(20)) / 20 * 1e3, 1),
-                "down_us": round(sum(ev[3 * k + 1].elapsed_time(ev[3 * k + 2]) for k in range(20)) / 20 * 1e3, 1),
-                "what": "torch.mm x2 on the same layer (plain GEMMs, context only)"}
-            del Wgu, hl, xl, o1, o2
+            for Tl in (4096, 512, 256, 64):
+                res["llama8b_T%d_library_gemms" % Tl] = library_gemms(torch, Wgu, dev[2], Tl)
+            del Wgu
         del x, dev
         torch.cuda.empty_cache()
     return res

@@ -75,7 +75,7 @@ fade_select(const uint32_t *__restrict__ hist, uint32_t *__restrict__ result, Fa
     __syncthreads();
     // inclusive scan over the 1024 partial sums
     for (int d = 1; d < 1024; d <<= 1) {
-        const unsigned long long add = threadIdx.x >= d ? part[threadIdx.x - d] : 0;
+        const unsigned long long add = (int)threadIdx.x >= d ? part[threadIdx.x - d] : 0;
         __syncthreads();
         part[threadIdx.x] += add;
         __syncthreads();
@@ -176,7 +176,7 @@ __device__ __forceinline__ void scan_for_ranks(const uint32_t *__restrict__ gh, 
     part[threadIdx.x] = mine;
     __syncthreads();
     for (int d = 1; d < 1024; d <<= 1) {
-        const unsigned long long add = threadIdx.x >= d ? part[threadIdx.x - d] : 0;
+        const unsigned long long add = (int)threadIdx.x >= d ? part[threadIdx.x - d] : 0;
         __syncthreads();
         part[threadIdx.x] += add;
         __syncthreads();
@@ -241,8 +241,7 @@ fade_histogram_f32_lo(const uint32_t *__restrict__ W, const unsigned long long *
 }
 
 __global__ void __launch_bounds__(1024)
-fade_select_f32_lo(const uint32_t *__restrict__ hist_lo, size_t hist_stride, unsigned long long *__restrict__ sel,
-                   FadeJobs jobs)
+fade_select_f32_lo(const uint32_t *__restrict__ hist_lo, size_t hist_stride, unsigned long long *__restrict__ sel)
 {
     __shared__ unsigned long long part[1024];
     __shared__ unsigned long long found[4];
@@ -505,7 +504,7 @@ hipError_t launch_fade_f32(void *W, const int32_t *off, const double *sparsity, 
     if (blocks < 1) blocks = 1;
     fade_histogram_f32_lo<<<dim3((unsigned)blocks, (unsigned)jobs.n), 256, 0, s>>>(Wc, sel, hist + kBins, hist_words, jobs);
     if (launch_status("fade_histogram_f32_lo launch") != hipSuccess) return hipErrorLaunchFailure;
-    fade_select_f32_lo<<<jobs.n, 1024, 0, s>>>(hist + kBins, hist_words, sel, jobs);
+    fade_select_f32_lo<<<jobs.n, 1024, 0, s>>>(hist + kBins, hist_words, sel);
     if (launch_status("fade_select_f32_lo launch") != hipSuccess) return hipErrorLaunchFailure;
     unsigned long long host_sel[MLPMOE_MAX_BRANCHES * kSelWords];
     const size_t sel_bytes = (size_t)jobs.n * kSelWords * sizeof(unsigned long long);

@@ -35,9 +35,9 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 # and reported as null when the source has changed since.
 TRAFFIC = {
     # (workload, kernel): (sha256 of the kernel's source file, bytes per launch = read + written, summary file)
-    # gate_up_mfma at T=4096: 1409.4 MB read (x is re-read once per group of 4 neuron tiles and the
+    # gate_up_mfma at T=4096: 1409.5 MB read (x is re-read once per group of 4 neuron tiles and the
     # weights once per XCD that needs them: 5.3x the 268 MB the kernel has to read) + 117.5 MB written
-    ("llama8b_T4096", "gate_up_mfma"): ("23043a12f8aa268e1979e59db3bc4d130e2fa22bed6180a57a9ab145711f132a", 1526.9e6,
+    ("llama8b_T4096", "gate_up_mfma"): ("bf0ed88be1d93a00e062ebef0a44bbe568df2dd17088321ee65f8b5ec3358ab5", 1527.0e6,
                                         "profiles/bench_llama8b_T4096_hbm_counters.md"),
     # decode gate+up at T=1: 235.8 MB read (the weights, once) + 0.1 MB written
     ("llama8b_T1", "decode_gate_up"): ("975659ba3cb068270946adf36a755d8bbb024b21a506aa9bb78ec2c0d8d2a01c", 235.9e6,

@@ -583,19 +583,24 @@ gate_up_mfma(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
     gate_up_tile<BMT, WM, NB, D, kStaged, kRouted>(X, Wg, Wu, H, T, d_model, ldh, route, bt, lds, tm, n0, n_end);
 }
 
-// The gate+up projection with WIDE tiles for the full rounds of 256 workgroups and NARROW tiles for what
-// is left, when that is at most half a round: the left-over wide tiles, cut in two, then fill one
-// (shorter) round of narrow tiles instead of leaving more than half of the CUs idle for a wide one.
+// The gate+up projection with WIDE tiles for the full rounds of 256 workgroups and smaller tiles for what
+// is left, when that is at most half a round: the left-over wide tiles, cut into REST pieces, then fill one
+// (shorter) round instead of leaving more than half of the CUs idle for a wide one.  REST = 2: halves of
+// 64 neurons (NARROW's tile); REST = 4, when at most a quarter of a round is left: quarters of 128 tokens x
+// 64 neurons, run by the same eight waves as 32 x (32 + 32) outputs each.
 // Workgroup ids below 8 * wide_per_xcd take wide tiles: id i is tile (i % 8) * P + i / 8 of the grouped
 // order, P = ids_per_xcd(wide tiles), i.e. every XCD works through the first wide_per_xcd tiles of its
-// contiguous eighth.  The ids above take the rest of each eighth, two ids (halves of 64 neurons) per
-// wide tile.  grid.x = 8 * (wide_per_xcd + 2 * (P - wide_per_xcd)).
-template <int WM>
+// contiguous eighth.  The ids above take the rest of each eighth, REST consecutive ids per wide tile (the
+// neuron half alternates fastest).  grid.x = 8 * (wide_per_xcd + REST * (P - wide_per_xcd)).
+constexpr int QUARTER_D = 3;                          // ring depth of the quarter tiles (7 parts of 16 KiB)
+template <int WM, int REST>
 __global__ void __launch_bounds__(WM * 128)
 gate_up_mfma_mixed(const uint16_t *__restrict__ X, const uint16_t *__restrict__ Wg,
                    const uint16_t *__restrict__ Wu, uint16_t *__restrict__ H, int T, int d_model, int ldh,
                    int tiles_m, int tiles_n, int wide_per_xcd, BranchTable bt)
 {
+    static_assert(REST == 2 || REST == 4, "halves or quarters of a wide tile");
+    static_assert(lds_bytes(BM / 2, 2, QUARTER_D) <= lds_bytes(BM, 4), "the quarter tiles' ring fits the wide tiles' LDS");
     __shared__ __attribute__((aligned(1024))) char lds[lds_bytes(BM, 4)];
     const int total = tiles_m * tiles_n;
     const int P = ids_per_xcd(total);
@@ -611,13 +616,20 @@ gate_up_mfma_mixed(const uint16_t *__restrict__ X, const uint16_t *__restrict__ 
         gate_up_tile<BM, WM, 4, 2, false, false>(X, Wg, Wu, H, T, d_model, ldh, nullptr, bt, lds, tm, n0, n_end);
     } else {
         k -= wide_per_xcd;
-        const int logical = xcd * P + wide_per_xcd + k / 2;
+        const int logical = xcd * P + wide_per_xcd + k / REST;
         if (logical >= xcd_end) return;
         tile_from_logical(logical, tiles_m, tiles_n, tm, tn);
         if (!neuron_tile(bt, tn, 128, n0, n_end)) return;
         n0 += (k % 2) * 64;
         if (n0 >= n_end) return;                                   // the run ends in the first half
-        gate_up_tile<BM, WM, 2, 2, false, false>(X, Wg, Wu, H, T, d_model, ldh, nullptr, bt, lds, tm, n0, n_end);
+        if (REST == 2) {
+            gate_up_tile<BM, WM, 2, 2, false, false>(X, Wg, Wu, H, T, d_model, ldh, nullptr, bt, lds, tm, n0, n_end);
+        } else {
+            const int tq = 2 * tm + (k % 4) / 2;                   // token tile of 128
+            if (tq * (BM / 2) >= T) return;                        // the last token tile ends in its first half
+            gate_up_tile<BM / 2, WM, 2, QUARTER_D, false, false>(X, Wg, Wu, H, T, d_model, ldh, nullptr, bt, lds, tq,
+                                                                 n0, n_end);
+        }
     }
 }
 
@@ -880,7 +892,7 @@ int k_tiles(const BranchTable &bt)
 // epilogue, hand-over) hidden under the main loop of the other, at 1.6 times WIDE's traffic into the
 // LDS per flop.  For layers and batches that give WIDE too few or too short tiles.
 // MIXED (gate+up only): WIDE for the full rounds of 256 workgroups, NARROW for a last round that WIDE tiles
-// would fill less than half.
+// would fill less than half; quarters of a wide tile (128 tokens x (64 + 64)) where they fit one round.
 // DEEP: SMALL's tile with four K tiles requested ahead instead of two (a ring of 9 parts, 144 KiB, one
 // workgroup per CU): for batches of a few dozen to a hundred tokens, where a launch has about one tile per
 // CU and is bound by how many bytes of weights it keeps in flight, not by the matrix cores.
@@ -950,6 +962,9 @@ int mixed_wide_per_xcd(long long wide_tiles)
     return (int)(rounds * (kCUs / XCDS));
 }
 
+// Pieces MIXED cuts each left-over wide tile into: quarters when they fit one round, else halves.
+int mixed_rest_parts(long long wide_tiles) { return wide_tiles % kCUs <= kCUs / 4 ? 4 : 2; }
+
 TileShape pick_gate_up_tile(const BranchTable &bt, int T, int d_model)
 {
     const int nk = ceil_div(d_model, BK);
@@ -966,8 +981,10 @@ TileShape pick_gate_up_tile(const BranchTable &bt, int T, int d_model)
         }
     }
     if (mixed_wide_per_xcd(wide) >= 0) {
-        // the full rounds as wide tiles, then one round of narrow ones
-        const double c = launch_cost_us(wide / kCUs * kCUs, nk, TILE_WIDE, 0.0) + launch_cost_us(kCUs, nk, TILE_NARROW, 0.0);
+        // the full rounds as wide tiles, then one round of narrow ones, or of quarters (measured 2 us shorter
+        // at 14 K tiles)
+        const double c = launch_cost_us(wide / kCUs * kCUs, nk, TILE_WIDE, 0.0) + launch_cost_us(kCUs, nk, TILE_NARROW, 0.0) -
+                         (mixed_rest_parts(wide) == 4 ? 2.0 : 0.0);
         if (c < best_cost * 0.97) best = TILE_MIXED;
     }
     return best;
@@ -1089,9 +1106,12 @@ static hipError_t launch_gate_up_mixed(const FwdArgs &a, const BranchTable &bt)
     for (int r = 0; r < bt.n_runs; ++r) tiles_n += ceil_div(bt.run_end[r] - bt.run_start[r], BNH_MAX);
     const int wide_per_xcd = mixed_wide_per_xcd(tiles_m * tiles_n);
     if (wide_per_xcd < 0) return note_hip_error("gate_up_mfma_mixed: tile count", hipErrorInvalidValue);
-    const long long grid = (long long)XCDS * (wide_per_xcd + 2LL * (ids_per_xcd(tiles_m * tiles_n) - wide_per_xcd));
+    const int rest_per_xcd = ids_per_xcd(tiles_m * tiles_n) - wide_per_xcd;
+    const int parts = mixed_rest_parts(tiles_m * tiles_n);
+    const long long grid = (long long)XCDS * (wide_per_xcd + (long long)parts * rest_per_xcd);
     ProfileScope ps(MLPMOE_KERNEL_GATE_UP_MFMA, a.stream);
-    gate_up_mfma_mixed<MFMA_WM><<<(unsigned)grid, MFMA_WM * 128, 0, a.stream>>>(
+    const auto kernel = parts == 4 ? gate_up_mfma_mixed<MFMA_WM, 4> : gate_up_mfma_mixed<MFMA_WM, 2>;
+    kernel<<<(unsigned)grid, MFMA_WM * 128, 0, a.stream>>>(
         static_cast<const uint16_t *>(a.x), static_cast<const uint16_t *>(a.Wg),
         static_cast<const uint16_t *>(a.Wu), static_cast<uint16_t *>(a.H), a.T, a.d_model, a.ldh, tiles_m,
         (int)tiles_n, wide_per_xcd, bt);

@@ -326,9 +326,10 @@ def test_first_k_sweep(mm, K):
 
 def test_bf16_mfma_mixed_tile_widths(mm):
     """More than one round of 256 wide tiles with a small remainder: the gate+up launch runs the full round
-    with 256 x (128 + 128) tiles and the remainder as halves of 64 neurons.  Ten token tiles (the last ragged),
-    three runs of active branches whose last wide tiles are 104, 88 and exactly 64 neurons wide (a second
-    half that is partly filled, and one that is empty)."""
+    with 256 x (128 + 128) tiles and the remainder (54 wide tiles, less than a quarter of a round) as quarters of
+    128 tokens x 64 neurons.  Ten token tiles (the last ragged: its second half holds no token), three runs of
+    active branches whose last wide tiles are 104, 88 and exactly 64 neurons wide (a second half that is partly
+    filled, and one that is empty)."""
     widths = [1000, 200, 1640, 1008, 8, 192]
     off = np.concatenate([[0], np.cumsum(widths)]).astype(np.int32)
     mask = [1, 0, 1, 1, 0, 1]
@@ -341,6 +342,15 @@ def test_bf16_mfma_mixed_tile_widths(mm):
     act = np.repeat(np.array(mask, bool), widths)
     assert np.array_equal(H[:, act], Hw[:, act])
     assert np.array_equal(got, run_gpu(*args, path=mm.PATH_MFMA_MIXED))
+    # a remainder of more than a quarter of a round (4 x 89 = 356 wide tiles: 100 left over) runs as halves
+    w2 = [5000, 304, 6200]
+    off2 = np.concatenate([[0], np.cumsum(w2)]).astype(np.int32)
+    args2 = small_bf16_case(79, 3 * 256 + 40, 64, off2.tolist(), [1, 0, 1])
+    got2, H2 = run_gpu_with_hidden(*args2, path=mm.PATH_MFMA_MIXED)
+    check_bf16_flip_aware(got2, H2, *args2, label="mixed tile widths, halves:")
+    wide2, Hw2 = run_gpu_with_hidden(*args2, path=mm.PATH_MFMA_WIDE)
+    act2 = np.repeat(np.array([1, 0, 1], bool), w2)
+    assert np.array_equal(H2[:, act2], Hw2[:, act2])
     # where the tile count leaves no such remainder the selector falls back to wide tiles
     small = small_bf16_case(78, 300, 64, [0, 1024], [1])
     assert np.array_equal(run_gpu(*small, path=mm.PATH_MFMA_MIXED), run_gpu(*small, path=mm.PATH_MFMA_WIDE))

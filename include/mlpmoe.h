@@ -71,8 +71,9 @@ enum {
     MLPMOE_PATH_MFMA_WIDE = 4,   /* 256 tokens x (128 + 128) neurons / 256 output features             */
     MLPMOE_PATH_MFMA_NARROW = 5, /* 256 tokens x (64 + 64) neurons / 128 output features               */
     MLPMOE_PATH_MFMA_SMALL = 6,  /* 128 tokens x (64 + 64) / 128, 4 waves, two workgroups per CU       */
-    MLPMOE_PATH_MFMA_MIXED = 7,  /* gate+up: WIDE for the full rounds of 256 workgroups, NARROW for a
-                                    remainder of at most half a round (WIDE if there is none); down: chosen */
+    MLPMOE_PATH_MFMA_MIXED = 7,  /* gate+up: WIDE for the full rounds of 256 workgroups; a remainder of at
+                                    most half a round as halves of a wide tile (NARROW's), of at most a
+                                    quarter of a round as quarters (WIDE if there is none); down: chosen */
     MLPMOE_PATH_MFMA_DEEP = 8,   /* SMALL's tile with four K tiles requested ahead, one workgroup per CU */
     MLPMOE_PATH_MFMA_SLIM = 9    /* 64 tokens x (64 + 64) / 128, 4 waves, five K tiles requested ahead   */
 };

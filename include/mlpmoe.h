@@ -206,8 +206,8 @@ MLPMOE_API int mlpmoe_forward_f32(const float *x, const float *W_gate, const flo
  * mlpmoe_forward_bf16_out_bf16 -- the bf16 forward with the result stored as bf16: out is
  * [T, d_model] bf16 (device, 16-byte aligned), each element the fp32 sum over branches rounded once
  * to nearest even.  Everything else (arguments, arithmetic up to that rounding, errors) is
- * mlpmoe_forward_bf16's, and so are the kernels, except that for T <= 16 and d_model >= 3072 the
- * float result adds the two halves of K separately, which can move a sum by a float rounding.  The rounding alone moves an element by up to 2^-9 of its magnitude, about
+ * mlpmoe_forward_bf16's, and so are the kernels, except that for T <= 16 the float result adds
+ * the two halves of K separately, which can move a sum by a float rounding.  The rounding alone moves an element by up to 2^-9 of its magnitude, about
  * 1e-2 of rms(out) for the largest elements: for callers whose next operation takes bf16 anyway
  * (Sec. 3.1 defines the sum; its storage precision is the caller's choice).  The _ws form takes a
  * caller-owned workspace and a path like mlpmoe_forward_bf16_ws and never allocates.

@@ -243,21 +243,24 @@ decode_kernel(const uint16_t *__restrict__ Xin, int ldx, int T,
     }
 }
 
-// Down projection for layers with many output features: two row tiles (32 output features) per
-// workgroup and the K blocks dealt to TWO workgroups (blockIdx.y).  Every workgroup of the one-tile
+// Down projection with RT row tiles (16 RT output features) per workgroup and the K blocks dealt to TWO
+// workgroups (blockIdx.y).  Layers with many output features take RT = 2:  Every workgroup of the one-tile
 // kernel reads all of H, which at 16 tokens is as many bytes as its weight rows, all from the same
 // L2; here a block of H is used for two weight fragments and each workgroup reads half of H, a quarter
 // of that traffic per weight byte, with all CUs still busy.  The two partial sums of an output are
 // added into `out` with float atomics: out must hold zeros when the kernel starts (the gate+up
 // kernel that runs before it clears it), and 0 + a + b is the same number in either order, so the
 // result does not depend on which workgroup comes first.
-template <int NW, int U, bool kRouted = false>
+// Narrow layers (few output features) take RT = 1 with 16 waves: twice the workgroups of the one-tile kernel,
+// and a wave's share of K short enough for its ring to hold all of it, so every weight byte is requested
+// as the kernel starts.
+template <int NW, int U, int RT, bool kRouted = false>
 __global__ void __launch_bounds__(NW * 64)
 decode_down_split(const uint16_t *__restrict__ Hin, int ldx, int T, const uint16_t *__restrict__ Wd, int ldw,
                   int d_model, float *__restrict__ out, const uint8_t *__restrict__ route, BranchTable bt)
 {
     static_assert(NW >= 4, "the final reduction uses 256 threads");
-    constexpr int RT = 2, KS = 2;
+    constexpr int KS = 2;
     __shared__ float red[NW][RT][256];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -488,7 +491,8 @@ constexpr int DEC_NW1 = 4, DEC_U1 = 8, DEC_NW2 = 8, DEC_U2 = 8, DEC_SNW = 8, DEC
 // K blocks w, w + NW, ... of EVERY tile, so the x fragments it needs are the same for every tile and
 // are loaded once, XB blocks of 2 x 16 bytes per lane (d_model <= 64 * NW * XB).  Everything else
 // (tile order, ring of U weight blocks rolling across tiles, reduction, epilogue, clear) is
-// decode_gate_up_persist's.
+// decode_gate_up_persist's.  XB < U (narrow layers): a revolution of the ring spans U / XB tiles, so the
+// weight blocks of that many tiles are in flight per wave and no slot is spent on blocks past d_model.
 template <int NW, int U, int XB, bool kRouted = false>
 __global__ void __launch_bounds__(NW * 64)
 decode_gate_up_xreg(const uint16_t *__restrict__ X, int T, const uint16_t *__restrict__ Wg,
@@ -497,7 +501,8 @@ decode_gate_up_xreg(const uint16_t *__restrict__ X, int T, const uint16_t *__res
 {
     if (clear)
         for (int i = blockIdx.x * (NW * 64) + threadIdx.x; i < clear_n; i += gridDim.x * (NW * 64)) clear[i] = 0.f;
-    static_assert(NW >= 4 && XB % U == 0, "the reduction uses 256 threads; ring slots are compile-time");
+    static_assert(NW >= 4 && (XB % U == 0 || U % XB == 0), "the reduction uses 256 threads; ring slots are compile-time");
+    constexpr int TPR = XB >= U ? 1 : U / XB;     // tiles per revolution of the ring
     __shared__ float red[2][NW][256];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -544,38 +549,47 @@ decode_gate_up_xreg(const uint16_t *__restrict__ X, int T, const uint16_t *__res
 
     int it = 0;
     TileCursor<kRouted> cur(st, blockIdx.x);
-    for (int row0 = cur.row0(st); row0 >= 0; cur.advance(st, gridDim.x), row0 = cur.row0(st), ++it) {
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    int row0 = cur.row0(st);
+    while (row0 >= 0) {
 #pragma unroll
-        for (int j0 = 0; j0 < XB; j0 += U) {
+        for (int tt = 0; tt < TPR; ++tt) {           // tile tt of this revolution uses ring slots tt * XB ...
+            if (row0 < 0) break;
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(wa[u][0]), as_bf16x8(xr[j0 + u][0]), acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(wa[u][1]), as_bf16x8(xr[j0 + u][1]), acc, 0, 0, 0);
-                load_next(u);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
-        float *rb = &red[it & 1][0][0];
+            for (int j0 = 0; j0 < XB; j0 += U) {
 #pragma unroll
-        for (int v = 0; v < 4; ++v) rb[wave * 256 + v * 64 + lane] = acc[v];
-        __syncthreads();
-        if (threadIdx.x < 256) {
-            const int v = threadIdx.x >> 6;
-            const int row = 4 * q + v;
-            if (row < 8 && tok) {
-                float g = 0.f, up = 0.f;
-#pragma unroll
-                for (int w = 0; w < NW; ++w) {
-                    g += rb[w * 256 + threadIdx.x];
-                    up += rb[w * 256 + threadIdx.x + 32];
+                for (int ju = 0; ju < (XB < U ? XB : U); ++ju) {
+                    const int u = XB < U ? tt * XB + ju : ju;
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(wa[u][0]), as_bf16x8(xr[j0 + ju][0]), acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(wa[u][1]), as_bf16x8(xr[j0 + ju][1]), acc, 0, 0, 0);
+                    load_next(u);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-                const int n = row0 + row;
-                const int b = branch_of(bt, n);
-                float v = bt.alpha[b] * silu_mul(g, up);
-                if (kRouted) v = route[(size_t)r16 * bt.B + b] ? v : 0.f;
-                Hout[(size_t)r16 * ldh + n] = to_bf16(v);
             }
+            float *rb = &red[it & 1][0][0];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) rb[wave * 256 + v * 64 + lane] = acc[v];
+            __syncthreads();
+            if (threadIdx.x < 256) {
+                const int v = threadIdx.x >> 6;
+                const int row = 4 * q + v;
+                if (row < 8 && tok) {
+                    float g = 0.f, up = 0.f;
+#pragma unroll
+                    for (int w = 0; w < NW; ++w) {
+                        g += rb[w * 256 + threadIdx.x];
+                        up += rb[w * 256 + threadIdx.x + 32];
+                    }
+                    const int n = row0 + row;
+                    const int b = branch_of(bt, n);
+                    float v = bt.alpha[b] * silu_mul(g, up);
+                    if (kRouted) v = route[(size_t)r16 * bt.B + b] ? v : 0.f;
+                    Hout[(size_t)r16 * ldh + n] = to_bf16(v);
+                }
+            }
+            ++it;
+            cur.advance(st, gridDim.x);
+            row0 = cur.row0(st);
         }
     }
 }
@@ -598,10 +612,10 @@ static hipError_t launch_decode_impl(const FwdArgs &a, const BranchTable &bt)
     const int nb_pad = ceil_div(ceil_div(ceil_div(a.d_model, KB), DEC_SNW), DEC_SU) * DEC_SU;
     const bool x_in_regs = nb_pad <= 16;                    // d_model <= 8192: x fragments stay in registers
     const bool persistent = x_in_regs || xs_bytes <= kStreamLdsMax;
-    // Layers with many output features take the down kernel that splits K over two workgroups and adds
-    // the halves into `out` with atomics; `out` is cleared by the persistent gate+up kernel, so the
-    // pair is only used together (and for a float result).
-    const bool split_down = tiles2 >= 192 && persistent && !a.out_bf16;
+    // A float result comes from the down kernel that splits K over two workgroups and adds the halves
+    // into `out` with atomics; `out` is cleared by the persistent gate+up kernel, so the pair is only used
+    // together.
+    const bool split_down = persistent && !a.out_bf16;
     float *clear = split_down ? a.out : nullptr;
     const int clear_n = split_down ? a.T * a.d_model : 0;
     const uint16_t *Wg = static_cast<const uint16_t *>(a.Wg), *Wu = static_cast<const uint16_t *>(a.Wu);
@@ -630,7 +644,14 @@ static hipError_t launch_decode_impl(const FwdArgs &a, const BranchTable &bt)
         }
         const int grid = tiles1 < n_cus ? (int)tiles1 : n_cus;
         ProfileScope ps(MLPMOE_KERNEL_DECODE_GATE_UP, a.stream);
-        if (nb_pad <= 8)
+        const int nb_wave = ceil_div(ceil_div(a.d_model, KB), DEC_SNW);      // K blocks per wave and tile
+        if (nb_wave <= 2)
+            decode_gate_up_xreg<DEC_SNW, DEC_SU, 2, kRouted><<<grid, DEC_SNW * 64, 0, a.stream>>>(
+                X, a.T, Wg, Wu, a.d_model, H, a.ldh, a.route, clear, clear_n, bt);
+        else if (nb_wave <= 4)
+            decode_gate_up_xreg<DEC_SNW, DEC_SU, 4, kRouted><<<grid, DEC_SNW * 64, 0, a.stream>>>(
+                X, a.T, Wg, Wu, a.d_model, H, a.ldh, a.route, clear, clear_n, bt);
+        else if (nb_pad <= 8)
             decode_gate_up_xreg<DEC_SNW, DEC_SU, 8, kRouted><<<grid, DEC_SNW * 64, 0, a.stream>>>(
                 X, a.T, Wg, Wu, a.d_model, H, a.ldh, a.route, clear, clear_n, bt);
         else if (nb_pad <= 16)
@@ -647,8 +668,11 @@ static hipError_t launch_decode_impl(const FwdArgs &a, const BranchTable &bt)
         if (launch_status("decode gate_up launch") != hipSuccess) return hipErrorLaunchFailure;
     }
     ProfileScope ps(MLPMOE_KERNEL_DECODE_DOWN, a.stream);
-    if (split_down)
-        decode_down_split<4, 8, kRouted><<<dim3(ceil_div(a.d_model, 32), 2), 4 * 64, 0, a.stream>>>(
+    if (split_down && tiles2 >= 192)
+        decode_down_split<4, 8, 2, kRouted><<<dim3(ceil_div(a.d_model, 32), 2), 4 * 64, 0, a.stream>>>(
+            H, a.ldh, a.T, static_cast<const uint16_t *>(a.Wd), a.d_inter, a.d_model, a.out, a.route, bt);
+    else if (split_down)
+        decode_down_split<16, 4, 1, kRouted><<<dim3(tiles2, 2), 16 * 64, 0, a.stream>>>(
             H, a.ldh, a.T, static_cast<const uint16_t *>(a.Wd), a.d_inter, a.d_model, a.out, a.route, bt);
     else if (tiles2 >= 192)
         decode_kernel<DEC_NW2, DEC_U2, false, kRouted><<<tiles2, DEC_NW2 * 64, 0, a.stream>>>(

@@ -4,7 +4,7 @@ Against the contract oracle rounded the same way, an element may differ by one b
 and the oracle's double sum fall on different sides of a rounding boundary, on top of the usual tolerance; so
 the bound per element is BF16_TOL * rms + one unit in the last place of the reference, and most elements
 must agree exactly.  The float result of the plain entry point, rounded on the host, must agree bit for bit
-(same kernels, same sums)."""
+where the kernels add up in the same order (prefill), and to one unit where they do not (decode)."""
 import numpy as np
 import pytest
 
@@ -29,7 +29,7 @@ def bf16_ulp(v):
     return np.ldexp(1.0, e - 8)
 
 
-def check(mm, L, off, alpha, mask, T, path=None):
+def check(mm, L, off, alpha, mask, T, path=None, same_sums=True):
     import torch
     x, Wg, Wu, Wd = (to_dev(a) for a in (L.x[:T], L.W_gate, L.W_up, L.W_down))
     out = torch.full((T, x.shape[1]), float("nan"), dtype=torch.bfloat16, device="cuda")
@@ -42,8 +42,13 @@ def check(mm, L, off, alpha, mask, T, path=None):
         f32 = mm.mlpmoe_forward_bf16_ws(x, Wg, Wu, Wd, off, alpha, mask, ws, path=path)
     got = out.to(torch.float64).cpu().numpy()
     assert np.all(np.isfinite(got))
-    # the same sums, rounded by the kernel or by the oracle's rule on the host: identical
-    assert np.array_equal(got, oracle.round_to_bf16(f32.cpu().numpy().astype(np.float64)))
+    # the same sums, rounded by the kernel or by the oracle's rule on the host: identical.  The decode kernels
+    # add the two halves of K separately for a float result and in one pass for a bf16 one: a unit apart at most
+    f32_rounded = oracle.round_to_bf16(f32.cpu().numpy().astype(np.float64))
+    if same_sums:
+        assert np.array_equal(got, f32_rounded)
+    else:
+        assert np.all(np.abs(got - f32_rounded) <= bf16_ulp(f32_rounded)) and np.mean(got == f32_rounded) >= 0.98
     ref = oracle.round_to_bf16(oracle.mlpmoe_forward(widen(L.x[:T]), widen(L.W_gate), widen(L.W_up),
                                                      widen(L.W_down), off, alpha, mask, mode="contract"))
     rms = float(np.sqrt(np.mean(ref * ref)))
@@ -59,7 +64,7 @@ def test_prefill_and_decode_paths(mm):
     alpha = L.alpha_draw
     check(mm, L, off, alpha, mask, 600)                    # MFMA kernels, K split (few output tiles)
     for T in (1, 7, 16):
-        check(mm, L, off, alpha, mask, T)                  # decode kernels
+        check(mm, L, off, alpha, mask, T, same_sums=False)  # decode kernels
     check(mm, L, off, alpha, mask, 600, path=mm.PATH_GENERIC)
     check(mm, L, off, alpha, mask, 16, path=mm.PATH_MFMA)
 

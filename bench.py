@@ -224,7 +224,7 @@ def library_gemms(torch, Wgu, Wd, T):
 def others(mm, synth, torch, seed):
     """Short runs of the remaining workloads: tokens/s and the fraction of the roofline that bounds them."""
     res = {}
-    for name, Ts in (("qwen05b", (2048, 1)), ("qwen05b_pruned", (2048, 16, 1)), ("llama8b_fade", (4096, 16, 1)),
+    for name, Ts in (("qwen05b", (2048, 1)), ("qwen05b_pruned", (2048, 16, 8, 1)), ("llama8b_fade", (4096, 16, 1)),
                      ("llama8b", (512, 256, 128, 64))):
         Tmax = max(Ts)
         L, x, dev, _, off, alpha, mask, d_eff = build_layer(mm, synth, name, Tmax, seed)

@@ -35,9 +35,9 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 # and reported as null when the source has changed since.
 TRAFFIC = {
     # (workload, kernel): (sha256 of the kernel's source file, bytes per launch = read + written, summary file)
-    # gate_up_mfma at T=4096: 1409.4 MB read (x is re-read once per group of 4 neuron tiles and the
+    # gate_up_mfma at T=4096: 1409.5 MB read (x is re-read once per group of 4 neuron tiles and the
     # weights once per XCD that needs them: 5.3x the 268 MB the kernel has to read) + 117.5 MB written
-    ("llama8b_T4096", "gate_up_mfma"): ("bf0ed88be1d93a00e062ebef0a44bbe568df2dd17088321ee65f8b5ec3358ab5", 1526.9e6,
+    ("llama8b_T4096", "gate_up_mfma"): ("74cf58c3161623bf36554d18cbcebfc1f69733b1bbae9467c73cc306b07d3fac", 1527.0e6,
                                         "profiles/bench_llama8b_T4096_hbm_counters.md"),
     # decode gate+up at T=1: 235.8 MB read (the weights, once) + 0.1 MB written
     ("llama8b_T1", "decode_gate_up"): ("86003e6bc49cbb5e7a657b5889afe067ff945beef544ca3f06cde8ec9f871dcf", 235.9e6,

@@ -633,7 +633,7 @@ gate_up_mfma_mixed(const uint16_t *__restrict__ X, const uint16_t *__restrict__ 
     }
 }
 
-// grid.x = splits * 8 * ids_per_xcd(tilesM * tilesN); dst = out (splits == 1) or partial[split][T][d_model].
+// grid.x = 8 * ids_per_xcd(splits * tilesM * tilesN); dst = out (splits == 1) or partial[split][T][d_model].
 // dst_mode: DST_F32 plain float stores; DST_BF16 (only with splits == 1) dst holds bf16 values, each sum
 // rounded once (RNE).
 // kRouted: the K loop of token tile tm walks only the branches some token of the tile is routed
@@ -646,10 +646,17 @@ down_mfma(const uint16_t *__restrict__ H, const uint16_t *__restrict__ Wd, float
 {
     static_assert(!kRouted || BMT == BM, "the routed path's tables are per 256 tokens");
     __shared__ __attribute__((aligned(1024))) char lds[lds_bytes(BMT, NB, D, kStaged)];
-    const int per_split = XCDS * ids_per_xcd((long long)tiles_m * tiles_n);
-    const int z = blockIdx.x / per_split;
+    // Work items are (split, tile in the grouped order), split slowest, and every XCD takes one contiguous
+    // eighth of that list: with K split, an XCD then works on few splits, whose slices of H and W_down are
+    // what its L2 has to hold (the 0.5B-shaped layer at T = 2048: 4.7 MB per XCD instead of 12.5 MB).
+    const int tiles = tiles_m * tiles_n;
+    const long long items = (long long)tiles * splits;
+    const int per_xcd = ids_per_xcd(items);
+    const long long item = (long long)(blockIdx.x % XCDS) * per_xcd + blockIdx.x / XCDS;
+    if (item >= items) return;
+    const int z = (int)(item / tiles);
     int tm, tn;
-    if (!tile_of(blockIdx.x % per_split, tiles_m, tiles_n, tm, tn)) return;
+    tile_from_logical((int)(item % tiles), tiles_m, tiles_n, tm, tn);
     constexpr int BNH = 32 * NB;                  // output features per B block; a tile has two
     const int t0 = tm * BMT, n0 = tn * (2 * BNH);
     KRunsLanes dyn{0, 0, 0};
@@ -1125,7 +1132,7 @@ static hipError_t launch_down(const FwdArgs &a, const BranchTable &bt, int split
     const int tiles_m = ceil_div(a.T, BMT);
     const int tiles_n = ceil_div(a.d_model, 64 * NB);
     const int kt_total = k_tiles(bt);
-    const long long grid = (long long)XCDS * ids_per_xcd((long long)tiles_m * tiles_n) * splits;
+    const long long grid = (long long)XCDS * ids_per_xcd((long long)tiles_m * tiles_n * splits);
     if (grid > 0x7fffffffLL) return note_hip_error("down_mfma grid", hipErrorInvalidValue);
     ProfileScope ps(MLPMOE_KERNEL_DOWN_MFMA, a.stream);
     down_mfma<BMT, WM, NB, S::D, S::kStaged, kRouted><<<(unsigned)grid, WM * 128, 0, a.stream>>>(
